@@ -1,0 +1,167 @@
+"""CPU oracle of one ISD step (test infrastructure only).
+
+Thin ctypes wrapper over `isd_oracle.c` (plain C, fp64).  Only tests/, the smoke
+check and the benchmark's cpu_baseline leg may import this package; the product
+path (paper_2604_11035_amd) never does.  Nothing here imports the product either.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_DIR = Path(__file__).resolve().parent
+_SRC = _DIR / "isd_oracle.c"
+_LIB = _DIR / "libisd_oracle.so"
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (-O2, OpenMP)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
+                               "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(str(_LIB))
+        L.isd_oracle_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.isd_oracle_philox4x32_10.restype = None
+        L.isd_oracle_accept_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.isd_oracle_accept_uniform.restype = C.c_double
+        L.isd_oracle_gumbel.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.isd_oracle_gumbel.restype = C.c_double
+        L.isd_oracle_attention.argtypes = [C.c_void_p] * 5 + [C.c_int32, C.c_void_p] + [C.c_int32] * 7 + \
+            [C.c_int64] * 3 + [C.c_double, C.c_int32, C.c_void_p]
+        L.isd_oracle_attention.restype = C.c_int
+        L.isd_oracle_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                        C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]
+        L.isd_oracle_accept.restype = C.c_int
+        L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.isd_oracle_row_stats.restype = C.c_int
+        L.isd_oracle_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().isd_oracle_num_threads())
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().isd_oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def accept_uniform(seed: int, offset: int, row: int) -> float:
+    return float(lib().isd_oracle_accept_uniform(seed, offset, row))
+
+
+def gumbel(seed: int, offset: int, row: int, i: int) -> float:
+    return float(lib().isd_oracle_gumbel(seed, offset, row, i))
+
+
+def attention(q, k_cache, v_cache, block_table, ctx_lens, S, *, Hq, Hkv, D, P,
+              scale=0.0, dtype=None, strides=None, sel=None, out=None) -> np.ndarray:
+    """Paged causal attention of S query rows per sequence; returns float64 [B,S,Hq,D].
+
+    q / k_cache / v_cache: float32 arrays, or uint16 arrays holding bf16 bits.
+    strides = (page_stride, head_stride, token_stride) in elements; default is the
+    contiguous [num_pages,Hkv,P,D] layout.
+    """
+    q = np.ascontiguousarray(q)
+    k_cache = np.ascontiguousarray(k_cache)
+    v_cache = np.ascontiguousarray(v_cache)
+    if dtype is None:
+        dtype = 1 if q.dtype == np.uint16 else 0
+    want = np.uint16 if dtype == 1 else np.float32
+    assert q.dtype == want and k_cache.dtype == want and v_cache.dtype == want
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    B = ctx_lens.shape[0]
+    assert q.size == B * S * Hq * D
+    max_pages = block_table.shape[1]
+    if strides is None:
+        num_pages = k_cache.size // (Hkv * P * D)
+        strides = (Hkv * P * D, P * D, D)
+    else:
+        num_pages = (k_cache.size - 1) // strides[0] + 1
+    if out is None:
+        out = np.full((B, S, Hq, D), np.nan, dtype=np.float64)
+    if sel is not None:
+        sel = np.ascontiguousarray(sel, dtype=np.uint8)
+        assert sel.size == B * Hkv
+    rc = lib().isd_oracle_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                    _ptr(ctx_lens), S, _ptr(out), B, Hq, Hkv, D, P, num_pages,
+                                    max_pages, strides[0], strides[1], strides[2], float(scale),
+                                    dtype, _ptr(sel))
+    if rc != 0:
+        raise ValueError("isd_oracle_attention failed: %d" % rc)
+    return out
+
+
+def accept(logits, draft_tokens, rng_seed, *, n_draft, greedy=None, rng_offset=0):
+    """Introspective acceptance over logits [B,S,V].
+
+    n_draft: int (same for every sequence) or int array [B].  greedy: None (all
+    stochastic) or uint8 [B].  Returns a dict with accept_len [B], new_tokens
+    [B,S], draft_probs [B,S-1] (float64) and the decision margins.
+    """
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, S, V = logits.shape
+    ncol = S - 1
+    dt = None
+    if S > 1:
+        dt = np.ascontiguousarray(draft_tokens, dtype=np.int32)[:, :ncol]
+        dt = np.ascontiguousarray(dt)
+        assert dt.shape == (B, ncol)
+    nd_arr, nd_uni = None, 0
+    if np.isscalar(n_draft):
+        nd_uni = int(n_draft)
+    else:
+        nd_arr = np.ascontiguousarray(n_draft, dtype=np.int32)
+        assert nd_arr.shape == (B,)
+    g = None if greedy is None else np.ascontiguousarray(greedy, dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32)
+    new_tokens = np.zeros((B, S), dtype=np.int32)
+    probs = np.zeros((B, max(ncol, 0)), dtype=np.float64)
+    margin = np.zeros((B, max(ncol, 0)), dtype=np.float64)
+    gap = np.zeros(B, dtype=np.float64)
+    runner = np.zeros(B, dtype=np.int32)
+    rc = lib().isd_oracle_accept(_ptr(logits), _ptr(dt), int(rng_seed), _ptr(accept_len),
+                                 _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(g),
+                                 int(rng_offset), _ptr(probs) if ncol else None,
+                                 _ptr(margin) if ncol else None, _ptr(gap), _ptr(runner))
+    if rc != 0:
+        raise ValueError("isd_oracle_accept failed: %d" % rc)
+    return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs,
+                accept_margin=margin, sample_gap=gap, runner_up=runner)
+
+
+def row_stats(row):
+    row = np.ascontiguousarray(row, dtype=np.float32)
+    m = C.c_double()
+    z = C.c_double()
+    a = C.c_int32()
+    rc = lib().isd_oracle_row_stats(_ptr(row), row.size, C.byref(m), C.byref(z), C.byref(a))
+    if rc != 0:
+        raise ValueError("isd_oracle_row_stats failed")
+    return m.value, z.value, a.value

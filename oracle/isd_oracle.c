@@ -1,0 +1,352 @@
+/*
+ * CPU oracle for one introspective-strided-decoding (ISD) step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, double-precision
+ * statement of what the two hot-path calls compute.  It is used by tests/, by
+ * the smoke check and by the benchmark's cpu_baseline leg, never by the product
+ * path, and it shares no code, header, table or helper with the HIP library.
+ *
+ * What is written out here:
+ *   - attention:  the definition of causal softmax attention of S query rows
+ *     per sequence over a paged KV cache (strict causal masking, Sec. 3.1
+ *     "Causal training with logit shift": key i visible to query j iff i <= j;
+ *     one paged extend of the stride's rows, Sec. 3.3 (1) and App. D).
+ *   - acceptance: Alg. 1's introspection loop, specialised to point-mass
+ *     (arg-max) proposals as deployed in Sec. 3.3 (3): accept test, accepted
+ *     prefix, resample from the residual on the first rejection, bonus token
+ *     when every draft passes, arg-max proposals from the MASK rows.
+ *   - the counter-based generator Philox4x32-10 (Salmon et al., SC'11) that
+ *     supplies the uniforms of the accept test and of the Gumbel-max sampler.
+ *
+ * Pins (tests that check this file against something other than itself) are in
+ * tests/test_oracle_*.py; every function here has at least one.
+ *
+ * No blocking, fusion or reordering: loops follow the definitions.  OpenMP is
+ * used only to run independent (sequence, head) / (sequence) items in parallel.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_TABLE (-2) /* a block-table entry that had to be read is out of range */
+
+/* ------------------------------------------------------------------------ */
+/* Philox4x32-10                                                              */
+/* ------------------------------------------------------------------------ */
+
+/* One call: 128-bit counter ctr[4], 64-bit key key[2] -> 4 output words.
+ * Ten rounds; each round multiplies counter words 0 and 2 by fixed odd
+ * constants, mixes high/low halves with the other words and the key, and the
+ * key is bumped by the Weyl constants between rounds. */
+void isd_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)M0 * c0;
+        uint64_t p1 = (uint64_t)M1 * c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* 32 random bits -> u in (0,1): u = (2*(x>>9) + 1) * 2^-24.  The numerator is an
+ * odd 24-bit integer, so u is exact in fp32 and never 0 or 1. */
+static double uniform_from_bits(uint32_t x)
+{
+    return (double)(2u * (x >> 9) + 1u) * (1.0 / 16777216.0);
+}
+
+/* Random word for vocabulary element i of logit row `row`:
+ * counter = (i>>2, row, stream, offset), key = (seed lo, seed hi), word i&3.
+ * stream 0 = accept-test uniform (element 0 only), stream 1 = Gumbel noise. */
+static uint32_t rng_word(uint64_t seed, uint32_t offset, uint32_t stream, uint32_t row, uint32_t i)
+{
+    uint32_t ctr[4] = { i >> 2, row, stream, offset };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    isd_oracle_philox4x32_10(ctr, key, out);
+    return out[i & 3u];
+}
+
+double isd_oracle_accept_uniform(uint64_t seed, uint32_t offset, uint32_t row)
+{
+    return uniform_from_bits(rng_word(seed, offset, 0u, row, 0u));
+}
+
+double isd_oracle_gumbel(uint64_t seed, uint32_t offset, uint32_t row, uint32_t i)
+{
+    double u = uniform_from_bits(rng_word(seed, offset, 1u, row, i));
+    return -log(-log(u));
+}
+
+/* ------------------------------------------------------------------------ */
+/* Attention                                                                  */
+/* ------------------------------------------------------------------------ */
+
+static double load_elem(const void* base, int64_t idx, int dtype)
+{
+    if (dtype == 0) return (double)((const float*)base)[idx];
+    /* bf16: the upper 16 bits of an IEEE fp32 */
+    uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/*
+ * out[b,i,h,:] = sum_t softmax_t(scale * <q[b,i,h,:], k_t[h/G,:]>) * v_t[h/G,:]
+ * over keys t = 0 .. ctx_lens[b]-S+i  (query row i sits at absolute position
+ * ctx_lens[b]-S+i; ctx_lens counts the S rows of this step, whose K/V are
+ * already in the pages).  Key t lives in page block_table[b][t/P], slot t%P.
+ *
+ * q   [B,S,Hq,D] contiguous; k_cache / v_cache: element (page,hk,slot,d) at
+ * page*page_stride + hk*head_stride + slot*token_stride + d (in elements).
+ * dtype 0 = fp32, 1 = bf16 bit patterns.  out is double [B,S,Hq,D].
+ * Only sequences/heads with sel==NULL or sel[b*Hkv+hk]!=0 are computed (others
+ * are left untouched) so that large workloads can be spot-checked.
+ */
+int isd_oracle_attention(const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* block_table, const int32_t* ctx_lens, int32_t S,
+                         double* out, int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                         int32_t num_pages, int32_t max_pages_per_seq, int64_t page_stride,
+                         int64_t head_stride, int64_t token_stride, double scale, int32_t dtype,
+                         const uint8_t* sel)
+{
+    if (!q || !k_cache || !v_cache || !block_table || !ctx_lens || !out) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || D < 1 || P < 1) return ORACLE_ERR_ARG;
+    if (dtype != 0 && dtype != 1) return ORACLE_ERR_ARG;
+    const int G = Hq / Hkv;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)D);
+    int status = ORACLE_OK;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        for (int hk = 0; hk < Hkv; ++hk) {
+            if (sel && !sel[b * Hkv + hk]) continue;
+            const int ctx = ctx_lens[b];
+            if (ctx < S || (ctx + P - 1) / P > max_pages_per_seq) {
+#pragma omp critical
+                status = ORACLE_ERR_ARG;
+                continue;
+            }
+            double* score = (double*)malloc((size_t)ctx * sizeof(double));
+            for (int i = 0; i < S; ++i) {
+                const int last = ctx - S + i; /* last visible key */
+                for (int g = 0; g < G; ++g) {
+                    const int h = hk * G + g;
+                    const int64_t qoff = (((int64_t)b * S + i) * Hq + h) * D;
+                    double smax = -INFINITY;
+                    int bad = 0;
+                    for (int t = 0; t <= last; ++t) {
+                        const int page = block_table[(int64_t)b * max_pages_per_seq + t / P];
+                        if (page < 0 || page >= num_pages) { bad = 1; break; }
+                        const int64_t koff = page * page_stride + hk * head_stride + (t % P) * token_stride;
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            dot += load_elem(q, qoff + d, dtype) * load_elem(k_cache, koff + d, dtype);
+                        score[t] = scale * dot;
+                        if (score[t] > smax) smax = score[t];
+                    }
+                    if (bad) {
+#pragma omp critical
+                        status = ORACLE_ERR_TABLE;
+                        continue;
+                    }
+                    double denom = 0.0;
+                    for (int t = 0; t <= last; ++t) {
+                        score[t] = exp(score[t] - smax);
+                        denom += score[t];
+                    }
+                    double* o = out + qoff;
+                    for (int d = 0; d < D; ++d) o[d] = 0.0;
+                    for (int t = 0; t <= last; ++t) {
+                        const int page = block_table[(int64_t)b * max_pages_per_seq + t / P];
+                        const int64_t voff = page * page_stride + hk * head_stride + (t % P) * token_stride;
+                        const double w = score[t] / denom;
+                        for (int d = 0; d < D; ++d) o[d] += w * load_elem(v_cache, voff + d, dtype);
+                    }
+                }
+            }
+            free(score);
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Introspective acceptance                                                   */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * One sequence b has S logit rows.  Row j < n_d is the causal anchor of drafted
+ * token j (the model's own next-token distribution at the position before that
+ * draft), row n_d is the anchor after the last draft (bonus token), rows > n_d
+ * come from MASK positions and propose next step's drafts.
+ *
+ * Steps, in Alg. 1's order, with the proposal distribution a point mass on the
+ * draft (arg-max proposals, Sec. 3.3 (3)), so min(1, p/q) = p(draft) and the
+ * residual normalize(max(0, p - q)) is p with the draft removed:
+ *   1. every row: m = max, Z = sum exp(l - m), a = lowest index attaining m
+ *   2. j < n_d: p_j = exp(l[draft_j] - m_j) / Z_j           -> draft_probs
+ *   3. accept test j < n_d: greedy: draft_j == a_j ; else u_j < p_j (strict)
+ *   4. accept_len r = number of leading accepted drafts
+ *   5. the one fresh token comes from row r:
+ *        greedy:      a_r
+ *        stochastic:  argmax_i (l_r[i] + gumbel_i), excluding i == draft_r iff r < n_d
+ *   6. new_tokens[j] = draft_j (j < r) | fresh token (j == r) | -1 (r < j <= n_d)
+ *                      | a_j (j > n_d)
+ *
+ * Diagnostic outputs (may be NULL) let a test decide whether a floating-point
+ * decision is far enough from its threshold to be compared bit-for-bit with a
+ * single-precision implementation:
+ *   accept_margin[b,j] = |u_j - p_j| for stochastic j < n_d (INFINITY otherwise)
+ *   sample_gap[b]      = best minus second-best perturbed score in row r
+ *                        (INFINITY for greedy sequences)
+ *   runner_up[b]       = index of that second-best element (-1 for greedy)
+ */
+int isd_oracle_accept(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                      int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                      int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                      uint32_t rng_offset, double* draft_probs, double* accept_margin,
+                      double* sample_gap, int32_t* runner_up)
+{
+    if (!logits || !accept_len || !new_tokens) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || V < 1) return ORACLE_ERR_ARG;
+    if (S > 1 && !draft_tokens) return ORACLE_ERR_ARG;
+    const int ncol = S - 1;
+    int status = ORACLE_OK;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int n_d = n_draft ? n_draft[b] : n_draft_uniform;
+        if (n_d < 0 || n_d > S - 1) {
+#pragma omp critical
+            status = ORACLE_ERR_ARG;
+            continue;
+        }
+        const int is_greedy = greedy ? (greedy[b] != 0) : 0;
+        double* m = (double*)malloc(sizeof(double) * S);
+        double* Z = (double*)malloc(sizeof(double) * S);
+        int32_t* a = (int32_t*)malloc(sizeof(int32_t) * S);
+
+        /* step 1 */
+        for (int j = 0; j < S; ++j) {
+            const float* l = logits + ((int64_t)b * S + j) * V;
+            double mx = -INFINITY;
+            int arg = 0;
+            for (int i = 0; i < V; ++i)
+                if ((double)l[i] > mx) { mx = (double)l[i]; arg = i; }
+            double z = 0.0;
+            for (int i = 0; i < V; ++i) z += exp((double)l[i] - mx);
+            m[j] = mx; Z[j] = z; a[j] = arg;
+        }
+
+        /* steps 2-4 */
+        int r = n_d;
+        int open = 1; /* still inside the accepted prefix */
+        for (int j = 0; j < ncol; ++j) {
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = 0.0;
+            if (accept_margin) accept_margin[(int64_t)b * ncol + j] = INFINITY;
+        }
+        for (int j = 0; j < n_d; ++j) {
+            const float* l = logits + ((int64_t)b * S + j) * V;
+            const int x = draft_tokens[(int64_t)b * ncol + j];
+            if (x < 0 || x >= V) {
+#pragma omp critical
+                status = ORACLE_ERR_ARG;
+                continue;
+            }
+            const double p = exp((double)l[x] - m[j]) / Z[j];
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = p;
+            int ok;
+            if (is_greedy) {
+                ok = (x == a[j]);
+            } else {
+                const double u = isd_oracle_accept_uniform(rng_seed, rng_offset, (uint32_t)(b * S + j));
+                ok = (u < p);
+                if (accept_margin) accept_margin[(int64_t)b * ncol + j] = fabs(u - p);
+            }
+            if (open && !ok) { r = j; open = 0; }
+        }
+        accept_len[b] = r;
+
+        /* step 5 */
+        int fresh;
+        double gap = INFINITY;
+        int second = -1;
+        if (is_greedy) {
+            fresh = a[r];
+        } else {
+            const float* l = logits + ((int64_t)b * S + r) * V;
+            const int excluded = (r < n_d) ? draft_tokens[(int64_t)b * ncol + r] : -1;
+            double best = -INFINITY, next = -INFINITY;
+            fresh = -1;
+            for (int i = 0; i < V; ++i) {
+                if (i == excluded) continue;
+                const double s = (double)l[i] + isd_oracle_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + r), (uint32_t)i);
+                if (s > best) { next = best; second = fresh; best = s; fresh = i; }
+                else if (s > next) { next = s; second = i; }
+            }
+            gap = best - next;
+        }
+        if (sample_gap) sample_gap[b] = gap;
+        if (runner_up) runner_up[b] = second;
+
+        /* step 6 */
+        for (int j = 0; j < S; ++j) {
+            int32_t tok;
+            if (j < r) tok = draft_tokens[(int64_t)b * ncol + j];
+            else if (j == r) tok = fresh;
+            else if (j <= n_d) tok = -1;
+            else tok = a[j];
+            new_tokens[(int64_t)b * S + j] = tok;
+        }
+        free(m); free(Z); free(a);
+    }
+    return status;
+}
+
+/* Row statistics alone (m, Z, arg-max) for spot checks of very large inputs. */
+int isd_oracle_row_stats(const float* row, int32_t V, double* m_out, double* z_out, int32_t* arg_out)
+{
+    if (!row || V < 1) return ORACLE_ERR_ARG;
+    double mx = -INFINITY;
+    int arg = 0;
+    for (int i = 0; i < V; ++i)
+        if ((double)row[i] > mx) { mx = (double)row[i]; arg = i; }
+    double z = 0.0;
+    for (int i = 0; i < V; ++i) z += exp((double)row[i] - mx);
+    if (m_out) *m_out = mx;
+    if (z_out) *z_out = z;
+    if (arg_out) *arg_out = arg;
+    return ORACLE_OK;
+}
+
+int isd_oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}
