@@ -1,0 +1,166 @@
+/*
+ * idlm.h - C ABI of the MI355X (gfx950) hot path of one introspective strided
+ * decoding (ISD) step: paged causal attention of a stride of S query rows per
+ * sequence, and the introspective acceptance pass over the step's logits.
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller unless stated
+ *     otherwise.  The library never allocates, frees or keeps a pointer past the
+ *     call; temporary storage comes from the caller's `workspace`.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  Outputs are valid once the caller has synchronised
+ *     that stream.  Two calls that share a workspace must be ordered by the
+ *     caller (same stream, or an event).
+ *   - Return value: IDLM_OK (0) or a negative IDLM_ERR_* code.  All arguments
+ *     that are visible to the host (pointers being NULL, shapes, strides,
+ *     alignment, workspace size) are checked before anything is launched, and
+ *     nothing is launched or written when a check fails.  The CONTENTS of device
+ *     arrays are preconditions that are not checked: ctx_lens[b] >= S and
+ *     ceil(ctx_lens[b]/P) <= max_pages_per_seq; block_table[b][p] in
+ *     [0,num_pages) for p < ceil(ctx_lens[b]/P) (entries beyond that are never
+ *     read); draft token ids in [0,V); n_draft[b] in [0,S-1]; logits hold no NaN.
+ *   - No global mutable state; entry points may be called from several host
+ *     threads.  No C++ exception crosses this boundary.
+ */
+#ifndef IDLM_H
+#define IDLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IDLM_VERSION 100 /* major*10000 + minor*100 + patch */
+
+enum {
+    IDLM_OK = 0,
+    IDLM_ERR_NULL = -1,      /* a required pointer is NULL */
+    IDLM_ERR_SHAPE = -2,     /* a size is out of the supported range */
+    IDLM_ERR_DTYPE = -3,     /* unknown dtype code, or dtype/shape combination not supported */
+    IDLM_ERR_ALIGN = -4,     /* a pointer or stride breaks the alignment the kernels need */
+    IDLM_ERR_WORKSPACE = -5, /* workspace missing or smaller than the *_workspace() size */
+    IDLM_ERR_LAUNCH = -6     /* the HIP runtime refused the launch (no device, bad stream, ...) */
+};
+
+enum {
+    IDLM_DTYPE_F32 = 0,
+    IDLM_DTYPE_BF16 = 1
+};
+
+/*
+ * idlm_isd_attention - causal attention of the step's S query rows over each
+ * sequence's paged KV cache and within the stride.
+ *
+ * Definition (strict causal masking: key position i is visible to query
+ * position j iff i <= j, Sec. 3.1 "Causal training with logit shift"; each ISD
+ * step is one paged "extend" of the stride's rows whose K/V are already in the
+ * pages, Sec. 3.3 (1) and App. D):
+ *   query row i of sequence b sits at absolute position ctx_lens[b]-S+i and
+ *   out[b,i,h,:] = sum_{t=0}^{ctx_lens[b]-S+i} softmax_t(scale * <q[b,i,h,:], K_t[h/G,:]>) * V_t[h/G,:]
+ *   with G = Hq/Hkv and key/value t of sequence b stored in page
+ *   block_table[b][t/P], slot t%P.  S = 1 is ordinary paged decode attention.
+ *
+ * q, out      [B,S,Hq,D] contiguous, element type `dtype`; 16-byte aligned.
+ * k_cache,    page pools; element (page, kv head, slot, d) is at
+ * v_cache     page*page_stride + head*head_stride + slot*token_stride + d (strides in
+ *             elements, the same for both pools).  [num_pages,Hkv,P,D] contiguous is
+ *             (Hkv*P*D, P*D, D); a token-major pool is (P*Hkv*D, D, Hkv*D).  16-byte
+ *             aligned base and strides.
+ * block_table int32 [B,max_pages_per_seq].
+ * ctx_lens    int32 [B]: KV length of each sequence INCLUDING this step's S rows.
+ * scale       softmax scale; <= 0 selects 1/sqrt(D).
+ * dtype       IDLM_DTYPE_BF16 (MFMA path; fp32 accumulation; D = 128; G = Hq/Hkv and S with
+ *             S*G <= 256) or IDLM_DTYPE_F32 (plain fp32 path; D in {64,128}).
+ * kv_chunk    tokens of one sequence handled by one workgroup; 0 = choose automatically.
+ *             Must be a multiple of 128 otherwise.  Sequences longer than one chunk are
+ *             split and merged through the workspace.
+ * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned; may be
+ *             NULL only when that size is 0.
+ * Supported: P = 16, 1 <= S <= 32, B >= 0 (B = 0 is a no-op).
+ */
+int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
+                       const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
+                       int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                       int32_t num_pages, int32_t max_pages_per_seq,
+                       int64_t page_stride, int64_t head_stride, int64_t token_stride,
+                       float scale, int32_t dtype, int32_t kv_chunk,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace idlm_isd_attention needs for these shapes (host-only, no GPU needed).
+ * Returns 0 for shapes that are rejected anyway. */
+size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                                    int32_t P, int32_t max_pages_per_seq, int32_t dtype,
+                                    int32_t kv_chunk);
+
+/* The kv_chunk that kv_chunk = 0 resolves to for these shapes (host-only). */
+int32_t idlm_isd_attention_auto_chunk(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
+                                      int32_t P, int32_t max_pages_per_seq, int32_t dtype);
+
+/*
+ * idlm_isd_accept - introspective acceptance over the step's logits.
+ *
+ * Sequence b has S logit rows.  Row j < n_d (n_d = its number of drafted tokens) is the
+ * model's own next-token distribution p_j ("causal anchor") for drafted token x_j, row n_d is
+ * the anchor after the last draft, rows > n_d come from MASK positions.  Following Alg. 1
+ * (introspection loop) with arg-max, i.e. point-mass, proposals as deployed in Sec. 3.3 (3),
+ * so that the accept probability min(1, p/q) is p_j(x_j) and the residual
+ * normalize(max(0, p - q)) is p_j with x_j removed (Sec. 3.2 "Adaptive stride via p/q
+ * acceptance"):
+ *   p_j        = softmax(logits[b,j,:])[x_j]                               (j < n_d)
+ *   accept_j   = greedy[b] ? (x_j == argmax logits[b,j,:]) : (u_{b,j} < p_j)
+ *   accept_len = number of leading accepted drafts, r in [0, n_d]
+ *   fresh token (row r): greedy: argmax of row r; otherwise Gumbel-max sample of row r,
+ *               with x_r excluded iff r < n_d (rejection); r = n_d is the bonus token
+ *   new_tokens[b,j] = x_j (j < r) | fresh token (j = r) | -1 (r < j <= n_d, discarded)
+ *                     | argmax logits[b,j,:] (j > n_d, next step's proposals)
+ * arg-max ties go to the lowest index.  Random numbers: Philox4x32-10 with key = (rng_seed
+ * low word, high word) and counter = (i >> 2, b*S+j, stream, rng_offset); element i uses
+ * output word i & 3; stream 0 word 0 of counter (0, row, 0, rng_offset) is the accept
+ * uniform, stream 1 feeds the Gumbel noise of vocabulary element i.  A 32-bit word x maps to
+ * u = (2*(x >> 9) + 1) * 2^-24 and g = -ln(-ln u).
+ *
+ * logits       fp32 [B,S,V] contiguous, 16-byte aligned; V % 4 == 0.
+ * draft_tokens int32 [B,S-1] (row stride S-1); entries j < n_d are read.  May be NULL iff S = 1.
+ * accept_len   int32 [B]   out.
+ * new_tokens   int32 [B,S] out.
+ * n_draft      int32 [B], or NULL to use n_draft_uniform (0 <= n_draft_uniform <= S-1) for all.
+ * greedy       uint8 [B] (non-zero = greedy), or NULL = every sequence stochastic.
+ * rng_offset   step counter; vary it between steps that reuse a seed.
+ * draft_probs  fp32 [B,S-1] out (p_j for j < n_d, 0 beyond), or NULL.
+ * workspace    at least idlm_isd_accept_workspace(B,S,V) bytes, 256-byte aligned.
+ * Supported: 1 <= S <= 64, 4 <= V < 2^31, B*S < 2^31; B = 0 is a no-op.
+ */
+int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                    int32_t* accept_len, int32_t* new_tokens,
+                    int32_t B, int32_t S, int32_t V,
+                    int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                    uint32_t rng_offset, float* draft_probs,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace idlm_isd_accept needs (host-only). Returns 0 for rejected shapes. */
+size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
+
+/* Static, NUL-terminated description of a return code (host pointer, never NULL). */
+const char* idlm_strerror(int code);
+
+/* IDLM_VERSION of the loaded library. */
+int idlm_version(void);
+
+/*
+ * Measurement aid: copies n_bytes from src to dst with 16-byte loads and stores (n_bytes a
+ * multiple of 16, both 16-byte aligned).  Used to calibrate hardware byte counters and to
+ * measure the streaming bandwidth actually reachable on the device.  Same stream / error
+ * conventions as above.
+ */
+int idlm_stream_copy(const void* src, void* dst, size_t n_bytes, void* stream);
+
+/* Measurement aid: reads n_bytes (multiple of 16, 16-byte aligned) and writes one 4-byte
+ * checksum word to *sink (device pointer): a read-only streaming pass. */
+int idlm_stream_read(const void* src, size_t n_bytes, uint32_t* sink, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IDLM_H */

@@ -1,0 +1,18 @@
+"""MI355X (gfx950) hot path of one introspective-strided-decoding step.
+
+Thin Python binding over the C ABI declared in include/idlm.h: the functions here
+only marshal arguments (device pointers, sizes, the current HIP stream); every
+step of the path runs in the hand-written HIP kernels of libidlm_isd.so.  There
+is no CPU or PyTorch fallback: if the library is missing, importing the binding
+functions raises.
+"""
+from .binding import (IdlmError, idlm_isd_accept, idlm_isd_accept_workspace,
+                      idlm_isd_attention, idlm_isd_attention_auto_chunk,
+                      idlm_isd_attention_workspace, idlm_stream_copy,
+                      idlm_stream_read, idlm_strerror, idlm_version, lib, lib_path)
+
+__all__ = [
+    "IdlmError", "idlm_isd_accept", "idlm_isd_accept_workspace", "idlm_isd_attention",
+    "idlm_isd_attention_auto_chunk", "idlm_isd_attention_workspace", "idlm_stream_copy",
+    "idlm_stream_read", "idlm_strerror", "idlm_version", "lib", "lib_path",
+]

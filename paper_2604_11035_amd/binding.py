@@ -1,0 +1,173 @@
+"""ctypes binding of libidlm_isd.so (same names as the C entry points)."""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libidlm_isd.so"
+_lib = None
+
+IDLM_DTYPE_F32 = 0
+IDLM_DTYPE_BF16 = 1
+
+
+class IdlmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %d (%s)" % (where, code, idlm_strerror(code)))
+
+
+def lib_path() -> Path:
+    return _LIB_PATH
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2604_11035_amd.build` "
+                "(or __graft_entry__.build())" % _LIB_PATH)
+        L = C.CDLL(str(_LIB_PATH))
+        i32, i64, vp = C.c_int32, C.c_int64, C.c_void_p
+        L.idlm_isd_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32,
+                                         i64, i64, i64, C.c_float, i32, i32, vp, C.c_size_t, vp]
+        L.idlm_isd_attention.restype = C.c_int
+        L.idlm_isd_attention_workspace.argtypes = [i32] * 9
+        L.idlm_isd_attention_workspace.restype = C.c_size_t
+        L.idlm_isd_attention_auto_chunk.argtypes = [i32] * 8
+        L.idlm_isd_attention_auto_chunk.restype = i32
+        L.idlm_isd_accept.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
+                                      vp, vp, C.c_size_t, vp]
+        L.idlm_isd_accept.restype = C.c_int
+        L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
+        L.idlm_isd_accept_workspace.restype = C.c_size_t
+        L.idlm_strerror.argtypes = [C.c_int]
+        L.idlm_strerror.restype = C.c_char_p
+        L.idlm_version.restype = C.c_int
+        L.idlm_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.idlm_stream_copy.restype = C.c_int
+        L.idlm_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+        L.idlm_stream_read.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def idlm_strerror(code: int) -> str:
+    return lib().idlm_strerror(int(code)).decode()
+
+
+def idlm_version() -> int:
+    return int(lib().idlm_version())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return IDLM_DTYPE_BF16
+    if t.dtype == torch.float32:
+        return IDLM_DTYPE_F32
+    raise TypeError("q/k/v must be bfloat16 or float32, got %s" % t.dtype)
+
+
+def idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, kv_chunk=0) -> int:
+    return int(lib().idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, kv_chunk))
+
+
+def idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype) -> int:
+    return int(lib().idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype))
+
+
+def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, scale=0.0, kv_chunk=0,
+                       workspace=None, stream=None):
+    """out[b,i,h,:] = causal attention of stride row i over the paged KV cache (see idlm.h).
+
+    q, out: [B,S,Hq,D]; k_cache, v_cache: [num_pages,Hkv,P,D] (any strides with a contiguous
+    last dimension); block_table int32 [B,max_pages]; ctx_lens int32 [B].  `workspace` is a
+    uint8 device tensor of at least idlm_isd_attention_workspace(...) bytes (may be None when
+    that is 0).  Asynchronous on `stream` (default: torch's current stream).
+    """
+    B, S_, Hq, D = q.shape
+    assert S_ == S and out.shape == q.shape and out.dtype == q.dtype
+    assert q.is_contiguous() and out.is_contiguous()
+    num_pages, Hkv, P, Dk = k_cache.shape
+    assert Dk == D and v_cache.shape == k_cache.shape and v_cache.stride() == k_cache.stride()
+    assert k_cache.stride(3) == 1 and k_cache.dtype == q.dtype and v_cache.dtype == q.dtype
+    assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert block_table.is_contiguous() and ctx_lens.is_contiguous() and block_table.shape[0] == B
+    rc = lib().idlm_isd_attention(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
+        B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
+        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale), _dtype_code(q),
+        int(kv_chunk), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_attention")
+    return out
+
+
+def idlm_isd_accept_workspace(B, S, V) -> int:
+    return int(lib().idlm_isd_accept_workspace(B, S, V))
+
+
+def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
+                    rng_offset=0, draft_probs=None, workspace=None, stream=None):
+    """Introspective acceptance over logits [B,S,V] (see idlm.h).
+
+    n_draft: int (uniform) or int32 device tensor [B]; greedy: uint8 device tensor [B] or None.
+    accept_len int32 [B] and new_tokens int32 [B,S] are written; draft_probs fp32 [B,S-1] optional.
+    """
+    B, S, V = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    assert accept_len.dtype == torch.int32 and new_tokens.dtype == torch.int32
+    assert accept_len.numel() == B and new_tokens.shape == (B, S) and new_tokens.is_contiguous()
+    if draft_tokens is not None:
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.is_contiguous()
+        assert S == 1 or draft_tokens.shape == (B, S - 1)
+    nd_ptr, nd_uni = None, 0
+    if isinstance(n_draft, torch.Tensor):
+        assert n_draft.dtype == torch.int32 and n_draft.numel() == B
+        nd_ptr = _ptr(n_draft)
+    else:
+        nd_uni = int(n_draft)
+    if greedy is not None:
+        assert greedy.dtype == torch.uint8 and greedy.numel() == B
+    if draft_probs is not None:
+        assert draft_probs.dtype == torch.float32 and draft_probs.is_contiguous()
+        assert draft_probs.numel() == B * (S - 1)
+    rc = lib().idlm_isd_accept(
+        _ptr(logits), _ptr(draft_tokens), int(rng_seed), _ptr(accept_len), _ptr(new_tokens),
+        B, S, V, nd_uni, nd_ptr, _ptr(greedy), int(rng_offset), _ptr(draft_probs),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_accept")
+    return accept_len, new_tokens
+
+
+def idlm_stream_copy(src, dst, stream=None):
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    rc = lib().idlm_stream_copy(_ptr(src), _ptr(dst), n, _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_stream_copy")
+
+
+def idlm_stream_read(src, sink, stream=None):
+    rc = lib().idlm_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_stream_read")

@@ -1,0 +1,82 @@
+// Error strings, version, and two plain streaming kernels used to calibrate byte counters and
+// to measure the bandwidth a pure copy / pure read reaches on the device.
+#include "idlm_common.h"
+
+namespace idlm {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink)
+{
+    const size_t T = (size_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * T < n16; i += 4 * T) {
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + T);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 2 * T), d = __builtin_nontemporal_load(src + i + 3 * T);
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += T) {
+        const u32x4 a = __builtin_nontemporal_load(src + i);
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    // fold the wavefront's words and let one lane per wavefront touch the sink: keeps every load alive
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) atomicXor(sink, acc);
+}
+
+}  // namespace idlm
+
+using namespace idlm;
+
+extern "C" const char* idlm_strerror(int code)
+{
+    switch (code) {
+        case IDLM_OK: return "ok";
+        case IDLM_ERR_NULL: return "a required pointer is NULL";
+        case IDLM_ERR_SHAPE: return "a size is outside the supported range";
+        case IDLM_ERR_DTYPE: return "unknown dtype or unsupported dtype/shape combination";
+        case IDLM_ERR_ALIGN: return "a pointer or stride is not aligned as required";
+        case IDLM_ERR_WORKSPACE: return "workspace missing or too small";
+        case IDLM_ERR_LAUNCH: return "the HIP runtime refused the launch";
+        default: return "unknown idlm error code";
+    }
+}
+
+extern "C" int idlm_version(void) { return IDLM_VERSION; }
+
+extern "C" int idlm_stream_copy(const void* src, void* dst, size_t n_bytes, void* stream)
+{
+    if (n_bytes == 0) return IDLM_OK;
+    if (!src || !dst) return IDLM_ERR_NULL;
+    if (n_bytes % 16) return IDLM_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return IDLM_ERR_ALIGN;
+    const size_t n16 = n_bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+    return launch_status();
+}
+
+extern "C" int idlm_stream_read(const void* src, size_t n_bytes, uint32_t* sink, void* stream)
+{
+    if (n_bytes == 0) return IDLM_OK;
+    if (!src || !sink) return IDLM_ERR_NULL;
+    if (n_bytes % 16) return IDLM_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return IDLM_ERR_ALIGN;
+    const size_t n16 = n_bytes / 16;
+    size_t blocks = (n16 + 1023) / 1024;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(src), n16, sink);
+    return launch_status();
+}

@@ -1,0 +1,154 @@
+"""GPU parity of idlm_isd_attention against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from isd_inputs import AttentionInputs, get_config, make_attention_inputs  # noqa: E402
+
+DEV = "cuda"
+
+
+def _helpers():
+    import helpers
+    return helpers
+
+
+def _check(inp, kv_chunk=0, sel=None, scale=0.0, tol=None):
+    h = _helpers()
+    got = h.gpu_attention(inp, kv_chunk=kv_chunk, scale=scale)
+    ref = h.oracle_attention(inp, sel=sel, scale=scale)
+    rel, nvec = h.attention_errors(got, ref)
+    tol = tol or (h.ATTN_REL_TOL if inp.q.dtype == torch.bfloat16 else h.ATTN_REL_TOL_F32)
+    assert nvec > 0
+    assert rel <= tol, "max relative error %g over %d vectors" % (rel, nvec)
+    print("max relative error %.3g over %d vectors" % (rel, nvec))
+    return got, ref
+
+
+def test_tiny_fp32():
+    inp = make_attention_inputs(get_config("tiny"), device=DEV, poison_unused=True)
+    _check(inp)
+
+
+@pytest.mark.parametrize("kv_chunk", [0, 128, 256, 1024])
+def test_small_model_bf16(kv_chunk):
+    inp = make_attention_inputs(get_config("small"), device=DEV, poison_unused=True)
+    _check(inp, kv_chunk=kv_chunk)
+
+
+def test_8b_class_bf16():
+    inp = make_attention_inputs(get_config("8b"), device=DEV, poison_unused=True)
+    _check(inp)
+
+
+def _sample_pairs(B, Hkv, n, seed):
+    rng = np.random.default_rng(seed)
+    sel = np.zeros((B, Hkv), dtype=np.uint8)
+    flat = rng.choice(B * Hkv, size=n, replace=False)
+    sel.reshape(-1)[flat] = 1
+    return sel
+
+
+def test_serving_config_full_size_sampled():
+    """B=256, S=16 with fragmented tables, auto chunking (what the benchmark times); the oracle
+    computes a seeded sample of (sequence, KV head) pairs plus the longest and shortest sequence."""
+    cfg = get_config("serve256")
+    inp = make_attention_inputs(cfg, device=DEV)
+    sel = _sample_pairs(cfg.B, cfg.Hkv, 12, 4)
+    ctx = inp.ctx_lens.cpu().numpy()
+    sel[int(ctx.argmax()), 0] = 1
+    sel[int(ctx.argmin()), 1] = 1
+    _check(inp, sel=sel)
+
+
+@pytest.mark.parametrize("S", [1, 4, 8, 16, 32])
+def test_long_context_stride_sweep_sampled(S):
+    cfg = get_config("long32k", S=S, B=4)
+    inp = make_attention_inputs(cfg, device=DEV)
+    sel = _sample_pairs(cfg.B, cfg.Hkv, 2 if S >= 16 else 3, S)
+    got, ref = _check(inp, sel=sel)
+    if S == 1:
+        # S = 1 is plain causal decode: one query at the last position sees every key
+        assert (inp.ctx_lens == 32768).all()
+
+
+def _manual(B, S, Hq, Hkv, ctx, dtype=torch.bfloat16, D=128, seed=0, token_major=False, extra_pages=2):
+    """Small hand-shaped inputs (ragged contexts, paddings) with NaN-poisoned unused slots."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    P = 16
+    pages = [(c + P - 1) // P for c in ctx]
+    num_pages = sum(pages) + extra_pages
+    perm = torch.randperm(num_pages, generator=g)
+    max_pages = max(pages) + 1
+    table = torch.full((B, max_pages), -1, dtype=torch.int32)
+    k = torch.full((num_pages, Hkv, P, D), float("nan"))
+    v = torch.full((num_pages, Hkv, P, D), float("nan"))
+    off = 0
+    for b in range(B):
+        for pi in range(pages[b]):
+            pg = int(perm[off]); off += 1
+            table[b, pi] = pg
+            nvalid = min(P, ctx[b] - pi * P)
+            k[pg, :, :nvalid] = torch.randn(Hkv, nvalid, D, generator=g)
+            v[pg, :, :nvalid] = torch.randn(Hkv, nvalid, D, generator=g)
+    q = torch.randn(B, S, Hq, D, generator=g)
+    k, v, q = k.to(dtype).to(DEV), v.to(dtype).to(DEV), q.to(dtype).to(DEV)
+    if token_major:
+        k = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # memory [pages,P,Hkv,D]
+        v = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    cfg = get_config("tiny")
+    return AttentionInputs(cfg, q, k, v, table.to(DEV), torch.tensor(ctx, dtype=torch.int32, device=DEV),
+                           num_pages, max_pages)
+
+
+@pytest.mark.parametrize("S,Hq,Hkv", [(1, 8, 1), (1, 8, 8), (3, 8, 2), (5, 8, 2), (4, 4, 2), (8, 32, 8),
+                                      (16, 16, 2), (32, 8, 1), (7, 6, 2), (32, 64, 8)])
+def test_row_paddings_and_group_sizes(S, Hq, Hkv):
+    ctx = [S, S + 1, 15 + S, 16 + S, 31 + S, 32 + S, 127 + S, 300]
+    inp = _manual(len(ctx), S, Hq, Hkv, ctx, seed=S * 100 + Hq)
+    for chunk in (0, 128):
+        _check(inp, kv_chunk=chunk)
+
+
+@pytest.mark.parametrize("ctx", [[128], [129], [256], [257], [255], [383, 384, 385], [1024, 1, 513]])
+def test_chunk_boundaries(ctx):
+    S = 1 if min(ctx) == 1 else 4
+    inp = _manual(len(ctx), S, 8, 2, ctx, seed=sum(ctx))
+    _check(inp, kv_chunk=128)
+    _check(inp, kv_chunk=256)
+
+
+def test_token_major_pool_and_explicit_scale():
+    inp = _manual(3, 4, 8, 2, [40, 200, 333], seed=5, token_major=True)
+    _check(inp, kv_chunk=128, scale=0.05)
+    _check(inp, scale=0.2)
+
+
+def test_fp32_path_shapes():
+    for D in (64, 128):
+        inp = _manual(3, 4, 4, 2, [4, 37, 120], dtype=torch.float32, D=D, seed=D)
+        _check(inp)
+
+
+def test_large_scores_do_not_overflow():
+    """Scores that grow along the context force the running reference exponent to be raised."""
+    inp = _manual(2, 4, 8, 2, [600, 333], seed=9)
+    ramp = torch.linspace(0.2, 6.0, 16, device=DEV).to(torch.bfloat16)
+    inp.k_cache.mul_(ramp[None, None, :, None])          # later slots of every page score higher
+    inp.q.mul_(4.0)
+    _check(inp, kv_chunk=128)
+
+
+def test_repeatable_and_empty_batch():
+    import paper_2604_11035_amd as idlm
+    h = _helpers()
+    inp = make_attention_inputs(get_config("small"), device=DEV)
+    a = h.gpu_attention(inp, kv_chunk=256)
+    b = h.gpu_attention(inp, kv_chunk=256)
+    assert np.array_equal(a, b)
+    q = torch.empty(0, 4, 8, 128, dtype=torch.bfloat16, device=DEV)
+    idlm.idlm_isd_attention(q, inp.k_cache, inp.v_cache, torch.empty(0, 4, dtype=torch.int32, device=DEV),
+                            torch.empty(0, dtype=torch.int32, device=DEV), 4, torch.empty_like(q))
+    torch.cuda.synchronize()
