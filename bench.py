@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the ISD-step hot path on one MI355X.
+
+One "step" = one idlm_isd_attention call (one layer's paged stride attention) plus one
+idlm_isd_accept call (introspective acceptance over the step's logits) on the large-
+concurrency serving workload (B=256, S=16; `serve256`), inputs resident in HBM.  Prints ONE
+JSON line: whole-step throughput in stride positions (tokens verified + proposed) per second,
+the roofline record of the dominant kernel (timed with HIP events recorded by the library
+around each of its kernels, on the stream they run on), and the CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+# HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
+# scaled by what the same counters read for idlm_stream_copy of known size); bytes per launch of
+# the named kernel on the named workload.  None where no measurement is committed under profiles/.
+MEASURED_TRAFFIC = {
+    ("serve256", "attention"): None,
+    ("serve256", "accept"): None,
+}
+
+
+class HipEvents:
+    """Minimal HIP event access (create / elapsed time) through libamdhip64."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def create(self, n):
+        out = []
+        for _ in range(n):
+            e = C.c_void_p()
+            rc = self.hip.hipEventCreate(C.byref(e))
+            if rc != 0:
+                raise RuntimeError("hipEventCreate failed: %d" % rc)
+            out.append(e.value)
+        return out
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b))
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+    def destroy(self, evs):
+        for e in evs:
+            self.hip.hipEventDestroy(C.c_void_p(e))
+
+
+def attention_algorithmic_bytes(ctx_lens, cfg):
+    """One read of every context token's K and V rows, Q in, O out, and the block table."""
+    kv = int(ctx_lens.sum()) * cfg.Hkv * cfg.D * 2 * 2
+    qo = cfg.B * 2 * cfg.S * cfg.Hq * cfg.D * 2
+    table = int(((ctx_lens + cfg.P - 1) // cfg.P).sum()) * 4
+    return kv + qo + table
+
+
+def attention_flops(ctx_lens, cfg):
+    """2 contractions x 2 flop x D per (query row, head, visible key)."""
+    vis = sum(int(c) - cfg.S + i + 1 for c in ctx_lens for i in range(cfg.S))
+    return 4 * cfg.D * cfg.Hq * vis
+
+
+def cpu_baseline(att, acc, cfg, n_seq):
+    """Times the oracle (as it stands) on the first n_seq sequences of the workload."""
+    import torch
+    import oracle
+    from isd_inputs import to_numpy
+
+    ctx = att.ctx_lens[:n_seq].cpu().numpy()
+    pages = (ctx + cfg.P - 1) // cfg.P
+    # compact the sample's pages into a small pool (pure data movement)
+    ids = torch.cat([att.block_table[b, :int(pages[b])] for b in range(n_seq)]).long()
+    k_small = att.k_cache.index_select(0, ids)
+    v_small = att.v_cache.index_select(0, ids)
+    table = np.full((n_seq, int(pages.max())), -1, dtype=np.int32)
+    off = 0
+    for b in range(n_seq):
+        table[b, :pages[b]] = np.arange(off, off + pages[b])
+        off += pages[b]
+    q = to_numpy(att.q[:n_seq])
+    k_np, v_np = to_numpy(k_small), to_numpy(v_small)
+    logits = to_numpy(acc.logits[:n_seq])
+    drafts = to_numpy(acc.draft_tokens[:n_seq])[:, :cfg.S - 1]
+    nd = to_numpy(acc.n_draft[:n_seq])
+    gr = to_numpy(acc.greedy[:n_seq])
+    oracle.lib()
+    t0 = time.perf_counter()
+    oracle.attention(q, k_np, v_np, table, ctx, cfg.S, Hq=cfg.Hq, Hkv=cfg.Hkv, D=cfg.D, P=cfg.P)
+    t1 = time.perf_counter()
+    oracle.accept(logits, drafts, acc.rng_seed, n_draft=nd, greedy=gr, rng_offset=acc.rng_offset)
+    t2 = time.perf_counter()
+    return {
+        "value": n_seq * cfg.S / (t2 - t0),
+        "unit": "tokens/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "first %d of %d sequences of serve256 (%d context tokens): attention %.2f s, acceptance %.2f s"
+                  % (n_seq, cfg.B, int(ctx.sum()), t1 - t0, t2 - t1),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="serve256")
+    ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--cpu-sample", type=int, default=16, help="sequences given to the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
+                 % args.gpus)
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import paper_2604_11035_amd as idlm
+    from isd_inputs import get_config, make_accept_inputs, make_attention_inputs
+
+    cfg = get_config(args.workload)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    att = make_attention_inputs(cfg, device=dev)
+    acc = make_accept_inputs(cfg, device=dev)
+    B, S, V = cfg.B, cfg.S, cfg.V
+    dcode = 1 if cfg.dtype == "bf16" else 0
+    max_pages = att.block_table.shape[1]
+    chunk = args.kv_chunk or idlm.idlm_isd_attention_auto_chunk(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages, dcode)
+    ws_att = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages,
+                                                                    dcode, args.kv_chunk)),
+                         dtype=torch.uint8, device=dev)
+    ws_acc = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(att.q)
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    new_tokens = torch.empty(B, S, dtype=torch.int32, device=dev)
+    draft_probs = torch.empty(B, max(S - 1, 1), dtype=torch.float32, device=dev)
+    drafts = acc.draft_tokens[:, :S - 1].contiguous() if S > 1 else None
+
+    hev = HipEvents()
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev_att=None, ev_acc=None):
+        idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
+                                kv_chunk=args.kv_chunk, workspace=ws_att, stream=stream, events=ev_att)
+        idlm.idlm_isd_accept(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft,
+                             greedy=acc.greedy, rng_offset=i, draft_probs=draft_probs if S > 1 else None,
+                             workspace=ws_acc, stream=stream, events=ev_acc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [(hev.create(3), hev.create(3)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i][0], events[i][1])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    def avg(which, a, b):
+        return sum(hev.elapsed_ms(e[which][a], e[which][b]) for e in events) / len(events)
+
+    t_att_main, t_att_merge = avg(0, 0, 1), avg(0, 1, 2)
+    t_acc_stats, t_acc_final = avg(1, 0, 1), avg(1, 1, 2)
+    for ea, eb in events:
+        hev.destroy(ea + eb)
+
+    ctx_np = att.ctx_lens.cpu().numpy().astype(np.int64)
+    att_bytes = attention_algorithmic_bytes(ctx_np, cfg)
+    acc_bytes = B * S * V * 4
+    att_flops = attention_flops(ctx_np, cfg)
+    kernels = {
+        "isd_attention_bf16_kernel": {
+            "ms": t_att_main, "algorithmic_bytes": att_bytes, "GBps": att_bytes / t_att_main / 1e6,
+            "frac_hbm": att_bytes / t_att_main / 1e6 / HBM_PEAK_GBS,
+            "TFLOPs": att_flops / t_att_main / 1e9, "frac_mfma": att_flops / t_att_main / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "kv_chunk": chunk},
+        "isd_attention_merge_kernel": {"ms": t_att_merge},
+        "isd_row_stats_kernel": {
+            "ms": t_acc_stats, "algorithmic_bytes": acc_bytes, "GBps": acc_bytes / t_acc_stats / 1e6,
+            "frac_hbm": acc_bytes / t_acc_stats / 1e6 / HBM_PEAK_GBS},
+        "isd_accept_finalize_kernel": {"ms": t_acc_final},
+    }
+    if t_att_main >= t_acc_stats:
+        dom, dom_name, dom_key = kernels["isd_attention_bf16_kernel"], "isd_attention_bf16_kernel", "attention"
+    else:
+        dom, dom_name, dom_key = kernels["isd_row_stats_kernel"], "isd_row_stats_kernel", "accept"
+    roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dom["GBps"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.workload, dom_key)),
+                "kernel": dom_name, "ms": dom["ms"]}
+
+    cpu = None
+    if args.cpu_sample > 0 and cfg.dtype == "bf16":
+        cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
+
+    line = {
+        "metric": "ISD tokens verified+proposed/sec at B=256 on 1 GPU; % of peak HBM GB/s",
+        "value": B * S / (ms_per_step / 1e3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: B=%d S=%d Hq=%d Hkv=%d D=%d P=%d V=%d, ctx %s [%d,%d] (sum %d), one attention "
+                               "layer + one acceptance pass per step"
+                               % (cfg.name, B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, V, cfg.ctx_kind, cfg.ctx_lo,
+                                  cfg.ctx_hi, int(ctx_np.sum())),
+                   "kv_chunk": chunk, "logits_dtype": "f32"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+        "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
+                          "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -88,6 +88,22 @@ int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
                        float scale, int32_t dtype, int32_t kv_chunk,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Same call with timing hooks: `events`, when not NULL, is a HOST array of three hipEvent_t
+ * (as void*) created by the caller; they are recorded on `stream` before the main kernel,
+ * between the main kernel and the merge kernel, and after the merge kernel, so that a
+ * benchmark can time each kernel of the call without a profiler.  events == NULL is exactly
+ * idlm_isd_attention.  For the fp32 path events[1] and events[2] are both recorded after its
+ * single kernel.
+ */
+int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
+                          int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                          int32_t num_pages, int32_t max_pages_per_seq,
+                          int64_t page_stride, int64_t head_stride, int64_t token_stride,
+                          float scale, int32_t dtype, int32_t kv_chunk,
+                          void* workspace, size_t workspace_bytes, void* stream, void* const* events);
+
 /* Bytes of workspace idlm_isd_attention needs for these shapes (host-only, no GPU needed).
  * Returns 0 for shapes that are rejected anyway. */
 size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
@@ -138,6 +154,15 @@ int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t r
                     int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
                     uint32_t rng_offset, float* draft_probs,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same call with timing hooks (see idlm_isd_attention_ev): three events, recorded before the
+ * row-statistics kernel, between it and the accept/sample kernel, and after the latter. */
+int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                       int32_t* accept_len, int32_t* new_tokens,
+                       int32_t B, int32_t S, int32_t V,
+                       int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                       uint32_t rng_offset, float* draft_probs,
+                       void* workspace, size_t workspace_bytes, void* stream, void* const* events);
 
 /* Bytes of workspace idlm_isd_accept needs (host-only). Returns 0 for rejected shapes. */
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);

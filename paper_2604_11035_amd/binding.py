@@ -38,6 +38,8 @@ def lib() -> C.CDLL:
         L.idlm_isd_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, i32,
                                          i64, i64, i64, C.c_float, i32, i32, vp, C.c_size_t, vp]
         L.idlm_isd_attention.restype = C.c_int
+        L.idlm_isd_attention_ev.argtypes = L.idlm_isd_attention.argtypes + [vp]
+        L.idlm_isd_attention_ev.restype = C.c_int
         L.idlm_isd_attention_workspace.argtypes = [i32] * 9
         L.idlm_isd_attention_workspace.restype = C.c_size_t
         L.idlm_isd_attention_auto_chunk.argtypes = [i32] * 8
@@ -45,6 +47,8 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                       vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept.restype = C.c_int
+        L.idlm_isd_accept_ev.argtypes = L.idlm_isd_accept.argtypes + [vp]
+        L.idlm_isd_accept_ev.restype = C.c_int
         L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_workspace.restype = C.c_size_t
         L.idlm_strerror.argtypes = [C.c_int]
@@ -92,14 +96,23 @@ def idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype)
     return int(lib().idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype))
 
 
+def _events_arg(events):
+    """Three hipEvent_t handles (ints) -> a host void*[3] for the *_ev entry points."""
+    if events is None:
+        return None
+    assert len(events) == 3
+    return (C.c_void_p * 3)(*[C.c_void_p(int(e)) for e in events])
+
+
 def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, scale=0.0, kv_chunk=0,
-                       workspace=None, stream=None):
+                       workspace=None, stream=None, events=None):
     """out[b,i,h,:] = causal attention of stride row i over the paged KV cache (see idlm.h).
 
     q, out: [B,S,Hq,D]; k_cache, v_cache: [num_pages,Hkv,P,D] (any strides with a contiguous
     last dimension); block_table int32 [B,max_pages]; ctx_lens int32 [B].  `workspace` is a
     uint8 device tensor of at least idlm_isd_attention_workspace(...) bytes (may be None when
-    that is 0).  Asynchronous on `stream` (default: torch's current stream).
+    that is 0).  Asynchronous on `stream` (default: torch's current stream).  `events`: optional
+    three hipEvent_t handles recorded around the call's kernels (idlm_isd_attention_ev).
     """
     B, S_, Hq, D = q.shape
     assert S_ == S and out.shape == q.shape and out.dtype == q.dtype
@@ -109,12 +122,12 @@ def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, sc
     assert k_cache.stride(3) == 1 and k_cache.dtype == q.dtype and v_cache.dtype == q.dtype
     assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
     assert block_table.is_contiguous() and ctx_lens.is_contiguous() and block_table.shape[0] == B
-    rc = lib().idlm_isd_attention(
+    rc = lib().idlm_isd_attention_ev(
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
         B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
         k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale), _dtype_code(q),
         int(kv_chunk), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
-        _stream(stream))
+        _stream(stream), _events_arg(events))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_attention")
     return out
@@ -125,7 +138,7 @@ def idlm_isd_accept_workspace(B, S, V) -> int:
 
 
 def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
-                    rng_offset=0, draft_probs=None, workspace=None, stream=None):
+                    rng_offset=0, draft_probs=None, workspace=None, stream=None, events=None):
     """Introspective acceptance over logits [B,S,V] (see idlm.h).
 
     n_draft: int (uniform) or int32 device tensor [B]; greedy: uint8 device tensor [B] or None.
@@ -149,11 +162,11 @@ def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n
     if draft_probs is not None:
         assert draft_probs.dtype == torch.float32 and draft_probs.is_contiguous()
         assert draft_probs.numel() == B * (S - 1)
-    rc = lib().idlm_isd_accept(
+    rc = lib().idlm_isd_accept_ev(
         _ptr(logits), _ptr(draft_tokens), int(rng_seed), _ptr(accept_len), _ptr(new_tokens),
         B, S, V, nd_uni, nd_ptr, _ptr(greedy), int(rng_offset), _ptr(draft_probs),
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
-        _stream(stream))
+        _stream(stream), _events_arg(events))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_accept")
     return accept_len, new_tokens

@@ -329,11 +329,12 @@ extern "C" size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V)
     return layout(B, S, make_plan(B, S, V)).total;
 }
 
-extern "C" int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                               int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
-                               int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
-                               const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
-                               void* workspace, size_t workspace_bytes, void* stream)
+extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                  int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                                  int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                  const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  void* const* events)
 {
     if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
     if (!n_draft && (n_draft_uniform < 0 || n_draft_uniform > S - 1)) return IDLM_ERR_SHAPE;
@@ -354,12 +355,26 @@ extern "C" int idlm_isd_accept(const float* logits, const int32_t* draft_tokens,
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     (void)hipGetLastError();
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     hipLaunchKernelGGL(isd_row_stats_kernel<8>, dim3((unsigned)(B * S * plan.nsplit)), dim3(256), 0, st,
                        logits, V, plan.chunk, plan.nsplit, S, stats, counters);
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const uint2 key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
     hipLaunchKernelGGL(isd_accept_finalize_kernel, dim3((unsigned)(B * plan.nsb)), dim3(256), 0, st,
                        logits, draft_tokens, key, accept_len, new_tokens, S, V, n_draft_uniform,
                        n_draft, greedy, rng_offset, draft_probs, stats, plan.nsplit, gpart, counters,
                        plan.nsb, plan.gchunk);
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
+}
+
+extern "C" int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                               int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                               int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                               const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    return idlm_isd_accept_ev(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
+                              n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
+                              workspace_bytes, stream, nullptr);
 }

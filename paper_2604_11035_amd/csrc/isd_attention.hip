@@ -514,12 +514,13 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
     return slots * 128 * sizeof(float) + slots * 2 * sizeof(float);
 }
 
-extern "C" int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
-                                  const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
-                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
-                                  int32_t num_pages, int32_t max_pages_per_seq, int64_t page_stride,
-                                  int64_t head_stride, int64_t token_stride, float scale, int32_t dtype,
-                                  int32_t kv_chunk, void* workspace, size_t workspace_bytes, void* stream)
+extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
+                                     const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
+                                     int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                                     int32_t num_pages, int32_t max_pages_per_seq, int64_t page_stride,
+                                     int64_t head_stride, int64_t token_stride, float scale, int32_t dtype,
+                                     int32_t kv_chunk, void* workspace, size_t workspace_bytes, void* stream,
+                                     void* const* events)
 {
     int err;
     if (!shapes_ok(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, &err)) return err;
@@ -547,8 +548,13 @@ extern "C" int idlm_isd_attention(const void* q, const void* k_cache, const void
         p.scale_log2 = scale * kLog2e;
         (void)hipGetLastError();
         dim3 grid(Hq, S, B);
+        if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
         if (D == 64) hipLaunchKernelGGL(isd_attention_f32_kernel<64>, grid, dim3(64), 0, st, p);
         else hipLaunchKernelGGL(isd_attention_f32_kernel<128>, grid, dim3(64), 0, st, p);
+        if (events) {
+            (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
+            (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
+        }
         return launch_status();
     }
 
@@ -577,6 +583,7 @@ extern "C" int idlm_isd_attention(const void* q, const void* k_cache, const void
     p.scale_log2 = scale * kLog2e;
 
     (void)hipGetLastError();
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     dim3 grid(p.nchunk, Hkv, B);
     const int nreg = 32 * NB + 2 * NB;
 #define IDLM_LAUNCH_ATTN(NB_, RG_, SLOTS_)                                                              \
@@ -595,6 +602,20 @@ extern "C" int idlm_isd_attention(const void* q, const void* k_cache, const void
     else if (RG == 2) IDLM_LAUNCH_ATTN(4, 2, 2);
     else IDLM_LAUNCH_ATTN(4, 4, 0);
 #undef IDLM_LAUNCH_ATTN
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     if (p.nchunk > 1) hipLaunchKernelGGL(isd_attention_merge_kernel, dim3(Hkv, B), dim3(256), 0, st, p);
+    if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
+}
+
+extern "C" int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
+                                  const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
+                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
+                                  int32_t num_pages, int32_t max_pages_per_seq, int64_t page_stride,
+                                  int64_t head_stride, int64_t token_stride, float scale, int32_t dtype,
+                                  int32_t kv_chunk, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return idlm_isd_attention_ev(q, k_cache, v_cache, block_table, ctx_lens, S, out, B, Hq, Hkv, D, P,
+                                 num_pages, max_pages_per_seq, page_stride, head_stride, token_stride,
+                                 scale, dtype, kv_chunk, workspace, workspace_bytes, stream, nullptr);
 }
