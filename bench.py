@@ -123,7 +123,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="serve256")
-    ap.add_argument("--kv-chunk", type=int, default=0)
+    ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
     ap.add_argument("--cpu-sample", type=int, default=16, help="sequences given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -145,9 +145,9 @@ def main():
     B, S, V = cfg.B, cfg.S, cfg.V
     dcode = 1 if cfg.dtype == "bf16" else 0
     max_pages = att.block_table.shape[1]
-    chunk = args.kv_chunk or idlm.idlm_isd_attention_auto_chunk(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages, dcode)
+    nwg = args.workgroups or torch.cuda.get_device_properties(0).multi_processor_count
     ws_att = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages,
-                                                                    dcode, args.kv_chunk)),
+                                                                    dcode)),
                          dtype=torch.uint8, device=dev)
     ws_acc = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=dev)
     out = torch.empty_like(att.q)
@@ -161,7 +161,7 @@ def main():
 
     def step(i, ev_att=None, ev_acc=None):
         idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
-                                kv_chunk=args.kv_chunk, workspace=ws_att, stream=stream, events=ev_att)
+                                num_workgroups=args.workgroups, workspace=ws_att, stream=stream, events=ev_att)
         idlm.idlm_isd_accept(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft,
                              greedy=acc.greedy, rng_offset=i, draft_probs=draft_probs if S > 1 else None,
                              workspace=ws_acc, stream=stream, events=ev_acc)
@@ -195,7 +195,7 @@ def main():
             "ms": t_att_main, "algorithmic_bytes": att_bytes, "GBps": att_bytes / t_att_main / 1e6,
             "frac_hbm": att_bytes / t_att_main / 1e6 / HBM_PEAK_GBS,
             "TFLOPs": att_flops / t_att_main / 1e9, "frac_mfma": att_flops / t_att_main / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-            "kv_chunk": chunk},
+            "workgroups": nwg},
         "isd_attention_merge_kernel": {"ms": t_att_merge},
         "isd_row_stats_kernel": {
             "ms": t_acc_stats, "algorithmic_bytes": acc_bytes, "GBps": acc_bytes / t_acc_stats / 1e6,
@@ -231,7 +231,7 @@ def main():
                                "layer + one acceptance pass per step"
                                % (cfg.name, B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, V, cfg.ctx_kind, cfg.ctx_lo,
                                   cfg.ctx_hi, int(ctx_np.sum())),
-                   "kv_chunk": chunk, "logits_dtype": "f32"},
+                   "attention_workgroups": nwg, "logits_dtype": "f32"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

@@ -73,25 +73,26 @@ enum {
  * scale       softmax scale; <= 0 selects 1/sqrt(D).
  * dtype       IDLM_DTYPE_BF16 (MFMA path; fp32 accumulation; D = 128; G = Hq/Hkv and S with
  *             S*G <= 256) or IDLM_DTYPE_F32 (plain fp32 path; D in {64,128}).
- * kv_chunk    tokens of one sequence handled by one workgroup; 0 = choose automatically.
- *             Must be a multiple of 128 otherwise.  Sequences longer than one chunk are
- *             split and merged through the workspace.
- * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned; may be
- *             NULL only when that size is 0.
- * Supported: P = 16, 1 <= S <= 32, B >= 0 (B = 0 is a no-op).
+ * num_workgroups  size of the persistent grid that shares the batch's 32-token tiles evenly;
+ *             0 = one workgroup per compute unit of the current device (the setting to use);
+ *             1..1024 forces a grid (testing, or leaving compute units to other streams).
+ * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned (bf16 path:
+ *             partial results of the (sequence, head) items that straddle two workgroups;
+ *             the fp32 path needs none and accepts NULL).
+ * Supported: P = 16, 1 <= S <= 32, 0 <= B <= 65535 (B = 0 is a no-op), B*max_pages_per_seq < 2^31.
  */
 int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
                        const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
                        int32_t num_pages, int32_t max_pages_per_seq,
                        int64_t page_stride, int64_t head_stride, int64_t token_stride,
-                       float scale, int32_t dtype, int32_t kv_chunk,
+                       float scale, int32_t dtype, int32_t num_workgroups,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Same call with timing hooks: `events`, when not NULL, is a HOST array of three hipEvent_t
  * (as void*) created by the caller; they are recorded on `stream` before the main kernel,
- * between the main kernel and the merge kernel, and after the merge kernel, so that a
+ * between the main kernel and the kernel that joins partial results, and after the latter, so that a
  * benchmark can time each kernel of the call without a profiler.  events == NULL is exactly
  * idlm_isd_attention.  For the fp32 path events[1] and events[2] are both recorded after its
  * single kernel.
@@ -101,18 +102,13 @@ int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cach
                           int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
                           int32_t num_pages, int32_t max_pages_per_seq,
                           int64_t page_stride, int64_t head_stride, int64_t token_stride,
-                          float scale, int32_t dtype, int32_t kv_chunk,
+                          float scale, int32_t dtype, int32_t num_workgroups,
                           void* workspace, size_t workspace_bytes, void* stream, void* const* events);
 
 /* Bytes of workspace idlm_isd_attention needs for these shapes (host-only, no GPU needed).
  * Returns 0 for shapes that are rejected anyway. */
 size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
-                                    int32_t P, int32_t max_pages_per_seq, int32_t dtype,
-                                    int32_t kv_chunk);
-
-/* The kv_chunk that kv_chunk = 0 resolves to for these shapes (host-only). */
-int32_t idlm_isd_attention_auto_chunk(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
-                                      int32_t P, int32_t max_pages_per_seq, int32_t dtype);
+                                    int32_t P, int32_t max_pages_per_seq, int32_t dtype);
 
 /*
  * idlm_isd_accept - introspective acceptance over the step's logits.

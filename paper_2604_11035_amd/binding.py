@@ -40,10 +40,8 @@ def lib() -> C.CDLL:
         L.idlm_isd_attention.restype = C.c_int
         L.idlm_isd_attention_ev.argtypes = L.idlm_isd_attention.argtypes + [vp]
         L.idlm_isd_attention_ev.restype = C.c_int
-        L.idlm_isd_attention_workspace.argtypes = [i32] * 9
+        L.idlm_isd_attention_workspace.argtypes = [i32] * 8
         L.idlm_isd_attention_workspace.restype = C.c_size_t
-        L.idlm_isd_attention_auto_chunk.argtypes = [i32] * 8
-        L.idlm_isd_attention_auto_chunk.restype = i32
         L.idlm_isd_accept.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                       vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept.restype = C.c_int
@@ -88,12 +86,8 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError("q/k/v must be bfloat16 or float32, got %s" % t.dtype)
 
 
-def idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, kv_chunk=0) -> int:
-    return int(lib().idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, kv_chunk))
-
-
-def idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype) -> int:
-    return int(lib().idlm_isd_attention_auto_chunk(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype))
+def idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype) -> int:
+    return int(lib().idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype))
 
 
 def _events_arg(events):
@@ -104,14 +98,14 @@ def _events_arg(events):
     return (C.c_void_p * 3)(*[C.c_void_p(int(e)) for e in events])
 
 
-def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, scale=0.0, kv_chunk=0,
+def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, scale=0.0, num_workgroups=0,
                        workspace=None, stream=None, events=None):
     """out[b,i,h,:] = causal attention of stride row i over the paged KV cache (see idlm.h).
 
     q, out: [B,S,Hq,D]; k_cache, v_cache: [num_pages,Hkv,P,D] (any strides with a contiguous
     last dimension); block_table int32 [B,max_pages]; ctx_lens int32 [B].  `workspace` is a
     uint8 device tensor of at least idlm_isd_attention_workspace(...) bytes (may be None when
-    that is 0).  Asynchronous on `stream` (default: torch's current stream).  `events`: optional
+    that is 0); num_workgroups = 0 means one persistent workgroup per compute unit.  Asynchronous on `stream` (default: torch's current stream).  `events`: optional
     three hipEvent_t handles recorded around the call's kernels (idlm_isd_attention_ev).
     """
     B, S_, Hq, D = q.shape
@@ -126,7 +120,7 @@ def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, sc
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
         B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
         k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale), _dtype_code(q),
-        int(kv_chunk), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        int(num_workgroups), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream), _events_arg(events))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_attention")

@@ -20,17 +20,17 @@ def bf16_to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def gpu_attention(inp, kv_chunk=0, scale=0.0):
+def gpu_attention(inp, num_workgroups=0, scale=0.0):
     """Runs idlm_isd_attention on `inp` (tensors must live on the GPU); returns float64 numpy."""
     cfg = inp.cfg
     out = torch.full_like(inp.q, float("nan"))
     dcode = 1 if inp.q.dtype == torch.bfloat16 else 0
     B, S, Hq, D = inp.q.shape
     Hkv, P = inp.k_cache.shape[1], inp.k_cache.shape[2]
-    nbytes = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, inp.block_table.shape[1], dcode, kv_chunk)
+    nbytes = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, inp.block_table.shape[1], dcode)
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=inp.q.device)
     idlm.idlm_isd_attention(inp.q, inp.k_cache, inp.v_cache, inp.block_table, inp.ctx_lens, S, out,
-                            scale=scale, kv_chunk=kv_chunk, workspace=ws)
+                            scale=scale, num_workgroups=num_workgroups, workspace=ws)
     torch.cuda.synchronize()
     return bf16_to_f64(out)
 

@@ -15,9 +15,9 @@ def _helpers():
     return helpers
 
 
-def _check(inp, kv_chunk=0, sel=None, scale=0.0, tol=None):
+def _check(inp, num_workgroups=0, sel=None, scale=0.0, tol=None):
     h = _helpers()
-    got = h.gpu_attention(inp, kv_chunk=kv_chunk, scale=scale)
+    got = h.gpu_attention(inp, num_workgroups=num_workgroups, scale=scale)
     ref = h.oracle_attention(inp, sel=sel, scale=scale)
     rel, nvec = h.attention_errors(got, ref)
     tol = tol or (h.ATTN_REL_TOL if inp.q.dtype == torch.bfloat16 else h.ATTN_REL_TOL_F32)
@@ -32,10 +32,12 @@ def test_tiny_fp32():
     _check(inp)
 
 
-@pytest.mark.parametrize("kv_chunk", [0, 128, 256, 1024])
-def test_small_model_bf16(kv_chunk):
+@pytest.mark.parametrize("num_workgroups", [0, 1, 7, 64, 1024])
+def test_small_model_bf16(num_workgroups):
+    """Different grids cut the tile list at different places: items are whole, split in two,
+    or spread over many workgroups (1024 workgroups: about one tile each)."""
     inp = make_attention_inputs(get_config("small"), device=DEV, poison_unused=True)
-    _check(inp, kv_chunk=kv_chunk)
+    _check(inp, num_workgroups=num_workgroups)
 
 
 def test_8b_class_bf16():
@@ -52,7 +54,7 @@ def _sample_pairs(B, Hkv, n, seed):
 
 
 def test_serving_config_full_size_sampled():
-    """B=256, S=16 with fragmented tables, auto chunking (what the benchmark times); the oracle
+    """B=256, S=16 with fragmented tables, default grid (what the benchmark times); the oracle
     computes a seeded sample of (sequence, KV head) pairs plus the longest and shortest sequence."""
     cfg = get_config("serve256")
     inp = make_attention_inputs(cfg, device=DEV)
@@ -108,21 +110,21 @@ def _manual(B, S, Hq, Hkv, ctx, dtype=torch.bfloat16, D=128, seed=0, token_major
 def test_row_paddings_and_group_sizes(S, Hq, Hkv):
     ctx = [S, S + 1, 15 + S, 16 + S, 31 + S, 32 + S, 127 + S, 300]
     inp = _manual(len(ctx), S, Hq, Hkv, ctx, seed=S * 100 + Hq)
-    for chunk in (0, 128):
-        _check(inp, kv_chunk=chunk)
+    for nwg in (0, 3):
+        _check(inp, num_workgroups=nwg)
 
 
 @pytest.mark.parametrize("ctx", [[128], [129], [256], [257], [255], [383, 384, 385], [1024, 1, 513]])
-def test_chunk_boundaries(ctx):
+def test_tile_and_slice_boundaries(ctx):
     S = 1 if min(ctx) == 1 else 4
     inp = _manual(len(ctx), S, 8, 2, ctx, seed=sum(ctx))
-    _check(inp, kv_chunk=128)
-    _check(inp, kv_chunk=256)
+    for nwg in (0, 1, 2, 5):
+        _check(inp, num_workgroups=nwg)
 
 
 def test_token_major_pool_and_explicit_scale():
     inp = _manual(3, 4, 8, 2, [40, 200, 333], seed=5, token_major=True)
-    _check(inp, kv_chunk=128, scale=0.05)
+    _check(inp, num_workgroups=4, scale=0.05)
     _check(inp, scale=0.2)
 
 
@@ -138,15 +140,16 @@ def test_large_scores_do_not_overflow():
     ramp = torch.linspace(0.2, 6.0, 16, device=DEV).to(torch.bfloat16)
     inp.k_cache.mul_(ramp[None, None, :, None])          # later slots of every page score higher
     inp.q.mul_(4.0)
-    _check(inp, kv_chunk=128)
+    _check(inp, num_workgroups=3)
+    _check(inp)
 
 
 def test_repeatable_and_empty_batch():
     import paper_2604_11035_amd as idlm
     h = _helpers()
     inp = make_attention_inputs(get_config("small"), device=DEV)
-    a = h.gpu_attention(inp, kv_chunk=256)
-    b = h.gpu_attention(inp, kv_chunk=256)
+    a = h.gpu_attention(inp)
+    b = h.gpu_attention(inp)
     assert np.array_equal(a, b)
     q = torch.empty(0, 4, 8, 128, dtype=torch.bfloat16, device=DEV)
     idlm.idlm_isd_attention(q, inp.k_cache, inp.v_cache, torch.empty(0, 4, dtype=torch.int32, device=DEV),
