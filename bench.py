@@ -200,7 +200,7 @@ def main():
         "isd_row_stats_kernel": {
             "ms": t_acc_stats, "algorithmic_bytes": acc_bytes, "GBps": acc_bytes / t_acc_stats / 1e6,
             "frac_hbm": acc_bytes / t_acc_stats / 1e6 / HBM_PEAK_GBS},
-        "isd_accept_finalize_kernel": {"ms": t_acc_final},
+        "isd_accept_chain+sample+emit_kernels": {"ms": t_acc_final},
     }
     if t_att_main >= t_acc_stats:
         dom, dom_name, dom_key = kernels["isd_attention_bf16_kernel"], "isd_attention_bf16_kernel", "attention"

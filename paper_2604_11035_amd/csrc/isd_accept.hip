@@ -1,10 +1,11 @@
 // Introspective acceptance pass of one ISD step (Alg. 1, introspection loop; fused
-// verification of Sec. 3.3 (3)) as two launches:
+// verification of Sec. 3.3 (3)) as four launches (the last three are tiny):
 //   1. row statistics: one streaming pass over every logit row (16-byte loads, online
 //      max / sum-of-exponentials / arg-max per thread, wavefront + LDS reductions);
-//   2. per sequence: accept tests, accepted-prefix length, proposals, and - only for
-//      stochastic sequences - a Gumbel-max pass over the single row that emits the fresh
-//      token, split over several workgroups and joined by the last one to finish.
+//   2. per sequence (one wavefront): accept tests, accepted-prefix length, proposals;
+//   3. only for stochastic sequences: a Gumbel-max pass over the single row that emits the
+//      fresh token, split over several workgroups that combine with one 64-bit atomic max;
+//   4. decode of the winning keys into new_tokens.
 // HBM-bound: the algorithmic traffic is one read of the logits (4*V bytes per row).
 #include "idlm_common.h"
 #include <limits.h>
@@ -20,10 +21,14 @@ struct RowPartial {   // statistics of one slice of one logit row
     int pad;
 };
 
-struct SamplePartial {
-    float score;
-    int idx;
-};
+// Best (score, index) of a sampled row as one 64-bit key whose unsigned order is "higher score
+// first, then lower index": workgroups of a row combine with a single atomic max, no fences.
+__device__ __forceinline__ unsigned long long sample_key(float score, int idx)
+{
+    const uint32_t bits = __float_as_uint(score);
+    const uint32_t ordered = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return ((unsigned long long)ordered << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)idx);
+}
 
 struct AcceptPlan {
     int chunk;    // vocabulary elements per workgroup in pass 1 (multiple of 1024)
@@ -47,8 +52,8 @@ static AcceptPlan make_plan(int32_t B, int32_t S, int32_t V)
     int64_t chunk = (((int64_t)V + nsplit - 1) / nsplit + 1023) / 1024 * 1024;
     p.chunk = (int)chunk;
     p.nsplit = (int)(((int64_t)V + chunk - 1) / chunk);
-    int64_t nsb = ((int64_t)V + 16383) / 16384;   // 16K elements of Philox + logs per workgroup
-    if (nsb > 32) nsb = 32;
+    int64_t nsb = ((int64_t)V + 4095) / 4096;     // 4K elements of Philox + logs per workgroup
+    if (nsb > 64) nsb = 64;
     int64_t gchunk = (((int64_t)V + nsb - 1) / nsb + 1023) / 1024 * 1024;
     p.gchunk = (int)gchunk;
     p.nsb = (int)(((int64_t)V + gchunk - 1) / gchunk);
@@ -58,7 +63,7 @@ static AcceptPlan make_plan(int32_t B, int32_t S, int32_t V)
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct AcceptWorkspace {
-    size_t stats_off, gpart_off, counter_off, total;
+    size_t stats_off, keys_off, chain_off, total;
 };
 
 static AcceptWorkspace layout(int32_t B, int32_t S, const AcceptPlan& p)
@@ -66,10 +71,9 @@ static AcceptWorkspace layout(int32_t B, int32_t S, const AcceptPlan& p)
     AcceptWorkspace w;
     w.stats_off = 0;
     size_t stats = (size_t)B * S * p.nsplit * sizeof(RowPartial);
-    w.gpart_off = align256(stats);
-    size_t gpart = (size_t)B * p.nsb * sizeof(SamplePartial);
-    w.counter_off = w.gpart_off + align256(gpart);
-    w.total = w.counter_off + align256((size_t)B * sizeof(uint32_t));
+    w.keys_off = align256(stats);
+    w.chain_off = w.keys_off + align256((size_t)B * sizeof(unsigned long long));   // one arg-max key per sequence
+    w.total = w.chain_off + align256((size_t)B * 2 * sizeof(int32_t));
     return w;
 }
 
@@ -94,8 +98,7 @@ __device__ __forceinline__ void combine_best(float& s, int& i, float s2, int i2)
 template <int UNROLL>
 __global__ __launch_bounds__(256) void isd_row_stats_kernel(const float* __restrict__ logits, int V,
                                                             int chunk, int nsplit, int S,
-                                                            RowPartial* __restrict__ stats,
-                                                            uint32_t* __restrict__ counters)
+                                                            RowPartial* __restrict__ stats)
 {
     const int row = blockIdx.x / nsplit;
     const int c = blockIdx.x - row * nsplit;
@@ -104,7 +107,6 @@ __global__ __launch_bounds__(256) void isd_row_stats_kernel(const float* __restr
     const int fbeg = (c * chunk) >> 2;
     const int fend = min(V, (c + 1) * chunk) >> 2;
 
-    if (c == 0 && tid == 0 && row % S == 0) counters[row / S] = 0u;
 
     float m = -INFINITY;   // running maximum of this thread's elements
     float z = 0.f;         // sum of 2^(l*log2e - ref_log2(m))
@@ -198,42 +200,46 @@ __device__ __forceinline__ float unit_uniform(uint32_t x)
     return (float)(2u * (x >> 9) + 1u) * 5.9604644775390625e-8f;
 }
 
-__device__ __forceinline__ float gumbel(uint32_t x) { return -logf(-logf(unit_uniform(x))); }
+// g = -ln(-ln u).  The inner logarithm must be accurate relative to its result for u close to 1
+// (the large noise values that decide the arg-max), so it is the library logf; the outer one only
+// needs absolute accuracy and is the hardware log2.
+__device__ __forceinline__ float gumbel(uint32_t x)
+{
+    const float t = -logf(unit_uniform(x));
+    return -0.69314718056f * __builtin_amdgcn_logf(t);
+}
 
-// ---- pass 2: accept chain, proposals, Gumbel-max sample -------------------------------------
+// ---- pass 2: accept chain and proposals, one wavefront per sequence ---------------------------
 
-__global__ __launch_bounds__(256) void isd_accept_finalize_kernel(
+struct ChainResult {   // what the sampling pass needs to know about a sequence
+    int row;           // stride row r that emits the fresh token, or -1 (greedy: nothing to sample)
+    int excluded;      // token id removed from the sample (the rejected draft), or -1
+};
+
+__global__ __launch_bounds__(64) void isd_accept_chain_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ draft_tokens, uint2 key,
     int32_t* __restrict__ accept_len, int32_t* __restrict__ new_tokens, int S, int V,
     int n_draft_uniform, const int32_t* __restrict__ n_draft, const uint8_t* __restrict__ greedy,
     uint32_t rng_offset, float* __restrict__ draft_probs, const RowPartial* __restrict__ stats,
-    int nsplit, SamplePartial* gpart, uint32_t* counters, int nsb, int gchunk)
+    int nsplit, ChainResult* __restrict__ chain, unsigned long long* __restrict__ keys)
 {
-    const int b = blockIdx.x / nsb;
-    const int c = blockIdx.x - b * nsb;
-    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;      // one lane per stride row (S <= 64)
     const bool is_greedy = greedy ? (greedy[b] != 0) : false;
-    if (is_greedy && c != 0) return;
     int n_d = n_draft ? n_draft[b] : n_draft_uniform;
     n_d = max(0, min(n_d, S - 1));
     const int ncol = S - 1;
 
-    __shared__ int s_arg[64];
-    __shared__ int s_ok[64];
-    __shared__ int s_r;
-    __shared__ float s_best[4];
-    __shared__ int s_bidx[4];
-
+    int a = 0, ok = 1, x = -1;
+    float p = 0.f;
     if (tid < S) {
         const int row = b * S + tid;
         const RowPartial* sp = stats + (size_t)row * nsplit;
         float m = sp[0].m, z = sp[0].z;
-        int a = sp[0].arg;
+        a = sp[0].arg;
         for (int k = 1; k < nsplit; ++k) combine_stats(m, z, a, sp[k].m, sp[k].z, sp[k].arg);
-        int ok = 1;
-        float p = 0.f;
         if (tid < n_d) {
-            const int x = draft_tokens[(size_t)b * ncol + tid];
+            x = draft_tokens[(size_t)b * ncol + tid];
             if (x >= 0 && x < V) {
                 const float lx = logits[(size_t)row * V + x];
                 p = fast_exp2(fmaf(lx, kLog2e, -ref_log2(m))) / z;
@@ -245,35 +251,49 @@ __global__ __launch_bounds__(256) void isd_accept_finalize_kernel(
                 ok = unit_uniform(w.x) < p;
             }
         }
-        if (c == 0 && draft_probs && tid < ncol) draft_probs[(size_t)b * ncol + tid] = p;
-        s_arg[tid] = a;
-        s_ok[tid] = ok;
+        if (draft_probs && tid < ncol) draft_probs[(size_t)b * ncol + tid] = p;
     }
-    __syncthreads();
+    // accepted prefix = rows below the first failed test
+    const unsigned long long failed = __ballot(tid < n_d && !ok);
+    const int r = failed ? (int)__builtin_ctzll(failed) : n_d;
+    const int a_r = __shfl(a, r);
+    const int x_r = __shfl(x, r);
+    if (tid < S) {
+        int tok;
+        if (tid < r) tok = x;
+        else if (tid == r) tok = a_r;
+        else if (tid <= n_d) tok = -1;
+        else tok = a;
+        if (tid != r || is_greedy) new_tokens[(size_t)b * S + tid] = tok;
+    }
     if (tid == 0) {
-        int r = n_d;
-        for (int j = 0; j < n_d; ++j)
-            if (!s_ok[j]) { r = j; break; }
-        s_r = r;
+        accept_len[b] = r;
+        ChainResult cr;
+        cr.row = is_greedy ? -1 : r;
+        cr.excluded = (r < n_d) ? x_r : -1;
+        chain[b] = cr;
+        keys[b] = 0ull;   // "nothing sampled yet"
     }
-    __syncthreads();
-    const int r = s_r;
-    if (c == 0) {
-        if (tid < S) {
-            int tok;
-            if (tid < r) tok = draft_tokens[(size_t)b * ncol + tid];
-            else if (tid == r) tok = s_arg[r];
-            else if (tid <= n_d) tok = -1;
-            else tok = s_arg[tid];
-            if (tid != r || is_greedy) new_tokens[(size_t)b * S + tid] = tok;
-        }
-        if (tid == 0) accept_len[b] = r;
-    }
-    if (is_greedy) return;
+}
+
+// ---- pass 3: Gumbel-max sample of the one row per stochastic sequence -------------------------
+
+__global__ __launch_bounds__(256) void isd_accept_sample_kernel(
+    const float* __restrict__ logits, uint2 key, int S, int V, uint32_t rng_offset,
+    const ChainResult* __restrict__ chain, unsigned long long* keys, int nsb, int gchunk)
+{
+    const int b = blockIdx.x / nsb;
+    const int c = blockIdx.x - b * nsb;
+    const int tid = threadIdx.x;
+    const ChainResult cr = chain[b];
+    if (cr.row < 0) return;           // greedy sequence: the chain kernel wrote everything
+
+    __shared__ float s_best[4];
+    __shared__ int s_bidx[4];
 
     // Gumbel-max over slice c of row r: argmax_i (l_i + g_i), the rejected draft excluded
-    const int excluded = (r < n_d) ? draft_tokens[(size_t)b * ncol + r] : -1;
-    const uint32_t row = (uint32_t)(b * S + r);
+    const int excluded = cr.excluded;
+    const uint32_t row = (uint32_t)(b * S + cr.row);
     const float4* __restrict__ p4 = reinterpret_cast<const float4*>(logits + (size_t)row * V);
     const int fbeg = (c * gchunk) >> 2;
     const int fend = min(V, (c + 1) * gchunk) >> 2;
@@ -301,21 +321,22 @@ __global__ __launch_bounds__(256) void isd_accept_finalize_kernel(
     __syncthreads();
     if (tid == 0) {
         for (int k = 1; k < 4; ++k) combine_best(best, bidx, s_best[k], s_bidx[k]);
-        SamplePartial sp;
-        sp.score = best; sp.idx = bidx;
-        gpart[(size_t)b * nsb + c] = sp;
-        __threadfence();                                  // publish the partial ...
-        const uint32_t ticket = atomicAdd(&counters[b], 1u);   // ... then take a ticket
-        if (ticket == (uint32_t)(nsb - 1)) {
-            __threadfence();                              // last to finish: see everyone's partial
-            float fs = -INFINITY;
-            int fi = INT_MAX;
-            const volatile SamplePartial* gp = gpart + (size_t)b * nsb;
-            for (int k = 0; k < nsb; ++k) combine_best(fs, fi, gp[k].score, gp[k].idx);
-            new_tokens[(size_t)b * S + r] = (fi == INT_MAX) ? -1 : fi;
-            counters[b] = 0u;
-        }
+        if (bidx != INT_MAX) atomicMax(&keys[b], sample_key(best, bidx));
     }
+}
+
+// ---- pass 4: decode the winning key of every stochastic sequence into its fresh token ----------
+
+__global__ __launch_bounds__(256) void isd_accept_emit_kernel(const ChainResult* __restrict__ chain,
+                                                              const unsigned long long* __restrict__ keys,
+                                                              int32_t* __restrict__ new_tokens, int B, int S)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    const ChainResult cr = chain[b];
+    if (cr.row < 0) return;
+    const unsigned long long k = keys[b];
+    new_tokens[(size_t)b * S + cr.row] = k ? (int32_t)(0xFFFFFFFFu - (uint32_t)k) : -1;
 }
 
 }  // namespace idlm
@@ -350,20 +371,23 @@ extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_toke
 
     char* ws = static_cast<char*>(workspace);
     RowPartial* stats = reinterpret_cast<RowPartial*>(ws + w.stats_off);
-    SamplePartial* gpart = reinterpret_cast<SamplePartial*>(ws + w.gpart_off);
-    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.counter_off);
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(ws + w.keys_off);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     hipLaunchKernelGGL(isd_row_stats_kernel<8>, dim3((unsigned)(B * S * plan.nsplit)), dim3(256), 0, st,
-                       logits, V, plan.chunk, plan.nsplit, S, stats, counters);
+                       logits, V, plan.chunk, plan.nsplit, S, stats);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const uint2 key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
-    hipLaunchKernelGGL(isd_accept_finalize_kernel, dim3((unsigned)(B * plan.nsb)), dim3(256), 0, st,
-                       logits, draft_tokens, key, accept_len, new_tokens, S, V, n_draft_uniform,
-                       n_draft, greedy, rng_offset, draft_probs, stats, plan.nsplit, gpart, counters,
-                       plan.nsb, plan.gchunk);
+    ChainResult* chain = reinterpret_cast<ChainResult*>(ws + w.chain_off);
+    hipLaunchKernelGGL(isd_accept_chain_kernel, dim3((unsigned)B), dim3(64), 0, st, logits, draft_tokens, key,
+                       accept_len, new_tokens, S, V, n_draft_uniform, n_draft, greedy, rng_offset, draft_probs,
+                       stats, plan.nsplit, chain, keys);
+    hipLaunchKernelGGL(isd_accept_sample_kernel, dim3((unsigned)(B * plan.nsb)), dim3(256), 0, st, logits, key,
+                       S, V, rng_offset, chain, keys, plan.nsb, plan.gchunk);
+    hipLaunchKernelGGL(isd_accept_emit_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, chain, keys,
+                       new_tokens, B, S);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
 }
