@@ -1,0 +1,116 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/idlm.h declares, and
+rejects bad host-visible arguments before touching the device (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2604_11035_amd as idlm
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "idlm.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(idlm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert {"idlm_isd_attention", "idlm_isd_accept", "idlm_isd_attention_workspace",
+            "idlm_isd_accept_workspace", "idlm_strerror", "idlm_version"} <= set(names)
+    L = idlm.lib()
+    for n in names:
+        assert getattr(L, n) is not None, n
+
+
+def test_version_and_error_strings():
+    assert idlm.idlm_version() == 100
+    seen = set()
+    for code in range(0, -7, -1):
+        msg = idlm.idlm_strerror(code)
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert "unknown" in idlm.idlm_strerror(-99)
+
+
+def test_workspace_sizes_are_host_only_and_monotone():
+    a = idlm.idlm_isd_accept_workspace(256, 16, 151936)
+    b = idlm.idlm_isd_accept_workspace(16, 8, 32768)
+    assert a > b > 0 and a % 256 == 0
+    assert idlm.idlm_isd_accept_workspace(4, 4, 1023) == 0          # V % 4 != 0 is rejected
+    assert idlm.idlm_isd_accept_workspace(4, 65, 1024) == 0
+    w = idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 1)
+    assert w > 0
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 0) == 0   # fp32 path needs none
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64 unsupported
+    assert idlm.idlm_isd_attention_workspace(256, 33, 32, 8, 128, 16, 512, 1) == 0
+
+
+FAKE = C.c_void_p(0x1000)        # non-NULL, 16-byte aligned, never dereferenced (validation only)
+ODD = C.c_void_p(0x1004)
+
+
+def _attention(**kw):
+    a = dict(q=FAKE, k=FAKE, v=FAKE, table=FAKE, ctx=FAKE, S=4, out=FAKE, B=2, Hq=8, Hkv=2, D=128, P=16,
+             num_pages=10, max_pages=4, ps=2 * 16 * 128, hs=16 * 128, ts=128, scale=0.0, dtype=1, nwg=0,
+             ws=None, ws_bytes=0, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_attention(a["q"], a["k"], a["v"], a["table"], a["ctx"], a["S"], a["out"], a["B"],
+                                         a["Hq"], a["Hkv"], a["D"], a["P"], a["num_pages"], a["max_pages"],
+                                         a["ps"], a["hs"], a["ts"], a["scale"], a["dtype"], a["nwg"], a["ws"],
+                                         a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(q=None), -1), (dict(out=None), -1), (dict(table=None), -1),
+    (dict(S=0), -2), (dict(S=33), -2), (dict(Hq=7), -2), (dict(P=32), -2), (dict(max_pages=0), -2),
+    (dict(S=32, Hq=32, Hkv=2), -2),            # S*G = 512 rows
+    (dict(nwg=-1), -2), (dict(nwg=5000), -2), (dict(ts=64), -2),
+    (dict(dtype=7), -3), (dict(D=64), -3), (dict(D=96, dtype=0), -3),
+    (dict(q=ODD), -4), (dict(k=ODD), -4), (dict(ts=132), -4),
+    (dict(), -5),                              # bf16 path without a workspace
+    (dict(ws=FAKE, ws_bytes=16), -5),
+])
+def test_attention_rejects_bad_arguments(kw, code):
+    assert _attention(**kw) == code
+
+
+def test_attention_empty_batch_is_ok_without_device():
+    assert _attention(B=0) == 0
+
+
+def _accept(**kw):
+    a = dict(logits=FAKE, drafts=FAKE, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024, ndu=1, nd=None,
+             greedy=None, off=0, probs=None, ws=None, ws_bytes=0, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_accept(a["logits"], a["drafts"], a["seed"], a["alen"], a["toks"], a["B"], a["S"],
+                                      a["V"], a["ndu"], a["nd"], a["greedy"], a["off"], a["probs"], a["ws"],
+                                      a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(logits=None), -1), (dict(alen=None), -1), (dict(toks=None), -1), (dict(drafts=None), -1),
+    (dict(S=0), -2), (dict(S=65), -2), (dict(V=1022), -2), (dict(V=0), -2), (dict(ndu=4), -2), (dict(ndu=-1), -2),
+    (dict(logits=ODD), -4),
+    (dict(), -5), (dict(ws=FAKE, ws_bytes=8), -5),
+])
+def test_accept_rejects_bad_arguments(kw, code):
+    assert _accept(**kw) == code
+
+
+def test_accept_empty_batch_and_single_row_without_drafts():
+    assert _accept(B=0) == 0
+    # S = 1 needs no draft array: gets past the NULL checks and stops at the missing workspace
+    assert _accept(S=1, ndu=0, drafts=None) == -5
+
+
+def test_stream_helpers_validate():
+    L = idlm.lib()
+    assert L.idlm_stream_copy(None, FAKE, 16, None) == -1
+    assert L.idlm_stream_copy(FAKE, FAKE, 10, None) == -2
+    assert L.idlm_stream_copy(ODD, FAKE, 16, None) == -4
+    assert L.idlm_stream_copy(FAKE, FAKE, 0, None) == 0
+    assert L.idlm_stream_read(FAKE, 32, None, None) == -1
