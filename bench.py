@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 # scaled by what the same counters read for idlm_stream_copy of known size); bytes per launch of
 # the named kernel on the named workload.  None where no measurement is committed under profiles/.
 MEASURED_TRAFFIC = {
-    ("serve256", "attention"): None,
-    ("serve256", "accept"): None,
+    ("serve256", "attention"): 3281553666,   # profiles/serve256_pmc_hbm_traffic.txt (1.011 x algorithmic)
+    ("serve256", "accept"): 2604232177,      # row-statistics kernel, same file (1.046 x algorithmic)
 }
 
 
@@ -124,7 +124,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="serve256")
     ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="sequences given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -210,6 +210,29 @@ def main():
                 "frac": dom["GBps"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.workload, dom_key)),
                 "kernel": dom_name, "ms": dom["ms"]}
 
+    # plain streaming kernels of known size: practical bandwidth ceiling of this device, and the
+    # reference that hardware byte counters are scaled by in the committed profiles
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    probe_dst = torch.empty_like(probe)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def timed(fn, n=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) / n
+
+    t_read = timed(lambda: idlm.idlm_stream_read(probe, sink))
+    t_copy = timed(lambda: idlm.idlm_stream_copy(probe, probe_dst))
+    stream_probe = {"read_GBps": probe.numel() / t_read / 1e6, "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6,
+              "bytes": probe.numel()}
+    del probe, probe_dst
+
     cpu = None
     if args.cpu_sample > 0 and cfg.dtype == "bf16":
         cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
@@ -235,6 +258,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "stream_ceiling": stream_probe,
         "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
                           "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }
