@@ -3,15 +3,16 @@
 // App. D) for gfx950.
 //
 // bf16 path.  Per KV head the work is the list of 32-token tiles of every sequence, in sequence
-// order.  The launch has one persistent workgroup per compute unit; workgroup w works on head
-// w % Hkv and owns slice w / Hkv of W / Hkv equal contiguous slices of that list ("stream-K"),
-// which it finds by itself with a block-wide prefix sum over ctx_lens: no host round trip, no
-// empty workgroups, equal bytes per compute unit whatever the length mix.  A slice is a run of
-// segments (one sequence, a tile range); a segment that covers its whole sequence writes the
-// final output, any other leaves an fp32 partial (at most two per workgroup) that a small
-// second kernel joins.
+// order.  The launch is persistent (one workgroup of four wavefronts per compute unit) and the
+// list is shared at wavefront level: wavefront v works on virtual head v % VH (a KV head and a
+// group of up to 64 query rows) and owns slice v / VH of NW / VH equal contiguous slices
+// ("stream-K"), which it finds with a block-wide prefix sum over ctx_lens: no host round trip,
+// no empty workgroups, equal bytes per wavefront whatever the length mix, and no barrier after
+// the prefix sum.  A sequence that lies wholly inside a slice is written out directly; one that
+// a slice boundary cuts leaves an fp32 partial (at most two per wavefront) that a small second
+// kernel joins.
 //
-// Inside a segment the S*G query rows that share the KV head form the N side of every MFMA and
+// For a tile the S*G query rows that share the KV head form the N side of every MFMA and
 // everything is computed transposed, so that no cross-lane data movement is needed between
 // the two contractions:
 //     St[token][row] = K[token][:] . Qt[:][row]          v_mfma_f32_16x16x32_bf16, A = K, B = Q
@@ -20,9 +21,7 @@
 // the B-operand layout of the second MFMA once the contraction index is numbered accordingly.
 // K rows are read from HBM directly in A-operand layout with 16-byte loads, and V rows are read
 // with 16-byte loads of full 256-byte rows and transposed inside each lane (8 tokens x 8 dims of
-// 16-bit values held by one lane).  The four wavefronts of a workgroup take the segment's tiles
-// round-robin (and, when S*G > 64, split the query rows), keep private online-softmax state
-// and are merged once through LDS at the end of the segment.
+// 16-bit values held by one lane).  Q operands of the wavefront's current sequence sit in LDS.
 //
 // HBM-bound for S*G below the machine's flop/byte ridge: algorithmic traffic is one read of
 // the sequence's K and V rows (2 * Hkv * D * 2 bytes per context token).
@@ -42,9 +41,9 @@ struct AttnParams {
     const uint16_t* k;
     const uint16_t* v;
     uint16_t* out;
-    float* ws_o;    // [2*W][Mpad][128] unnormalised partial outputs (slot 2w: first segment of
-    float* ws_ml;   // [2*W][Mpad][2]   workgroup w, 2w+1: its last) and (reference exponent, denominator)
-    int B, S, Hq, Hkv, G, M, max_pages, Mpad;
+    float* ws_o;    // [2*NW][Mpad][128] unnormalised partial outputs (slot 2v: first sequence of
+    float* ws_ml;   // [2*NW][Mpad][2]   wavefront v's slice, 2v+1: its last) and (reference exponent, denominator)
+    int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
 };
@@ -53,11 +52,6 @@ struct AttnParams {
 // than this many powers of two: probabilities then stay below 2^12, harmless in fp32 / bf16
 // (bf16 has fp32's exponent range), and after the first tile the rescale almost never runs.
 constexpr float kRescaleSlack = 12.0f;
-
-struct KVTile {
-    bf16x8 k[2][4];   // [16-token block][k-step]: A operand of St
-    u32x4 v[8];       // [slot j']: token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
-};
 
 // ---- the tile list and its partition -------------------------------------------------------
 
@@ -126,63 +120,124 @@ __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* 
 // The block table and the context lengths are separate __restrict__ kernel arguments: nothing
 // the kernel stores can alias them, so their wave-uniform loads stay on the scalar unit and do
 // not tie up the vector-memory counter that the K/V prefetch relies on.
-template <int NB, int RG>
-__global__ __launch_bounds__(256, (NB <= 2 ? 2 : 1)) void isd_attention_bf16_kernel(const AttnParams p,
+//
+// Work is shared at WAVEFRONT level.  A "virtual head" is (KV head, group of 16*NB query rows);
+// with NW wavefronts in the launch, wavefront v works on virtual head v % VH and owns slice
+// v / VH of NW / VH equal contiguous slices of the per-head tile list.  After the common
+// prefix sum the four wavefronts of a workgroup never synchronise again: each streams its
+// slice tile by tile, switching sequence (new Q, fresh accumulators, output written) whenever
+// the slice crosses into the next one, with the next tile's K/V always in flight - also across
+// such a switch.
+template <int NB>
+__global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParams p,
                                                                  const int32_t* __restrict__ block_table,
                                                                  const int32_t* __restrict__ ctx_lens)
 {
-    constexpr int TS = 4 / RG;            // wavefronts that split the tiles of one row group
-    constexpr int NREG = 32 * NB + 2 * NB;
-    extern __shared__ float lds[];
+    extern __shared__ u32x4 qlds_all[];   // [wavefront][(nb*4 + s)*64 + lane] Q operands of the current item
     __shared__ TilePlan plan;
 
-    // ---- this workgroup's head and its slice of that head's tile list ----
-    // W >= Hkv: workgroup w works on head w % Hkv and takes slice w / Hkv of Wg = W / Hkv equal
-    // slices of the per-head tile list.  Workgroups w, w+1, .. of one slice index run side by side
-    // and read the Hkv adjacent 4 KB head blocks of the same pages at about the same time
-    // (DRAM row and TLB locality).  W < Hkv: workgroup w takes heads w, w+W, .. whole.
     const int total = plan_scan(p, ctx_lens, plan);
-    const int W = gridDim.x, wg = blockIdx.x;
-    const int Wg = W >= p.Hkv ? W / p.Hkv : 1;
-    const int slice = W >= p.Hkv ? wg / p.Hkv : 0;
-    const int head0 = W >= p.Hkv ? wg % p.Hkv : wg;
-    const int head_step = W >= p.Hkv ? p.Hkv : W;
-    if (slice >= Wg) return;
-    const int slice_begin = (int)((int64_t)total * slice / Wg), slice_end = (int)((int64_t)total * (slice + 1) / Wg);
-    if (slice_begin >= slice_end) return;
-    int b0, pre0;
-    plan_locate(p, ctx_lens, plan, slice_begin, b0, pre0);
-
+    if (total == 0) return;
     const int lane = threadIdx.x & 63;
     const int w = wave_id();
-    const int rg = w / TS, ts = w % TS;
+    const int NW = gridDim.x * 4;
+    const int VH = p.Hkv * p.RG;
+    const int Wg = NW >= VH ? NW / VH : 1;
+    auto slice_of = [&](int v) { return NW >= VH ? v / VH : 0; };
+    auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
+
+    // first sequence of every wavefront's slice (the lookup is block-wide: all four take part)
+    const int wv = blockIdx.x * 4 + w;
+    int b0 = 0, pre0 = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int jk = slice_of(blockIdx.x * 4 + k);
+        const int xk = (jk < Wg) ? slice_start(jk) : 0;
+        int bk, prek;
+        plan_locate(p, ctx_lens, plan, min(xk, total - 1), bk, prek);
+        if (k == w) { b0 = bk; pre0 = prek; }
+    }
+    const int slice = slice_of(wv);
+    if (slice >= Wg) return;
+    const int slice_begin = slice_start(slice), slice_end = slice_start(slice + 1);
+    if (slice_begin >= slice_end) return;
+    const int vh0 = NW >= VH ? wv % VH : wv;
+    const int vstep = NW >= VH ? VH : NW;
+
     const int n = lane & 15, g = lane >> 4;
-    const int rowbase = rg * 16 * NB;
     const int S = p.S, G = p.G, M = p.M;
     const float cs = p.scale_log2;
+    u32x4* const qlds = qlds_all + (size_t)w * (NB * 4 * 64) + lane;
 
-    int qpos[NB];   // stride position i of this lane's row in each 16-row block
+    for (int vh = vh0; vh < VH; vh += vstep) {
+        const int kvh = vh / p.RG;
+        const int rowbase = (vh - kvh * p.RG) * 16 * NB;
+        int qpos[NB];   // stride position i of this lane's row in each 16-row block
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) qpos[nb] = (rowbase + 16 * nb + n) / G;
-    u32x4* qlds = reinterpret_cast<u32x4*>(lds) + (size_t)rg * NB * 4 * 64;
+        for (int nb = 0; nb < NB; ++nb) qpos[nb] = (rowbase + 16 * nb + n) / G;
+        const uint16_t* kh = p.k + kvh * p.head_stride;
+        const uint16_t* vhp = p.v + kvh * p.head_stride;
 
-    for (int kvh = head0; kvh < p.Hkv; kvh += head_step) {
-    int b = b0;
-    int ntiles = seq_tiles(p, ctx_lens, b);
-    int seg_a = slice_begin - pre0;
-    int pos = slice_begin;
-    bool first_segment = true;
+        // Page ids of tile kt of sequence b (two 16-token pages).  The second id is only read when
+        // that page belongs to the sequence; otherwise the first page is read again and masked out.
+        auto page_ids = [&](int b, int kt, int& pg0, int& pg1) {
+            const int32_t* __restrict__ tab = block_table + (size_t)b * p.max_pages;
+            const int npages = (min(ctx_lens[b], p.max_pages * 16) + 15) >> 4;
+            pg0 = tab[2 * kt];
+            pg1 = (2 * kt + 1 < npages) ? tab[2 * kt + 1] : pg0;
+        };
+        // next tile of the slice: the next tile of the sequence, or tile 0 of the next non-empty one
+        auto advance = [&](int& b, int& kt, int& nt) {
+            if (++kt == nt) {
+                kt = 0;
+                do { ++b; nt = seq_tiles(p, ctx_lens, b); } while (nt == 0);
+            }
+        };
+        bf16x8 tk[2][4];   // K of the current tile: [16-token block][k-step], A operand of St
+        u32x4 tv[8];       // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
+        auto load_k = [&](int pg0, int pg1) {
+            const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride + n * p.token_stride + g * 8;
+            const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride + n * p.token_stride + g * 8;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                tk[0][s] = *reinterpret_cast<const bf16x8*>(k0 + 32 * s);
+                tk[1][s] = *reinterpret_cast<const bf16x8*>(k1 + 32 * s);
+            }
+        };
+        auto load_v = [&](int pg0, int pg1) {
+            const uint16_t* v0 = vhp + (size_t)pg0 * p.page_stride + (4 * g) * p.token_stride + n * 8;
+            const uint16_t* v1 = vhp + (size_t)pg1 * p.page_stride + (4 * g) * p.token_stride + n * 8;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tv[j] = *reinterpret_cast<const u32x4*>(v0 + j * p.token_stride);
+                tv[4 + j] = *reinterpret_cast<const u32x4*>(v1 + j * p.token_stride);
+            }
+        };
 
-    while (pos < slice_end) {
-        const int seg_b = min(ntiles, seg_a + (slice_end - pos));   // tiles [seg_a, seg_b) of item (b, kvh)
-        const bool complete = seg_a == 0 && seg_b == ntiles;
-        const int ctx = min(ctx_lens[b], p.max_pages * 16);
-        const int npages = (ctx + 15) >> 4;
+        // cursors: current tile (b, kt of nt); c1 = next tile of the slice, whose page ids are held in
+        // (npg0, npg1).  K/V loads are issued unconditionally (the compiler can then count the
+        // outstanding loads exactly and waits for K without waiting for V and vice versa); the very
+        // last tile of the slice simply requests itself again.
+        int b = b0, nt = seq_tiles(p, ctx_lens, b), kt = slice_begin - pre0;
+        const int remaining = slice_end - slice_begin;
+        int c1b = b, c1kt = kt, c1nt = nt, npg0, npg1;
+        page_ids(b, kt, npg0, npg1);
+        load_k(npg0, npg1);
+        load_v(npg0, npg1);
+        if (remaining > 1) {
+            advance(c1b, c1kt, c1nt);
+            page_ids(c1b, c1kt, npg0, npg1);
+        }
 
-        // ---- Q as B operands, parked in LDS: lane (row n, group g) of k-step s holds dims
-        //      8*(4s+g) .. +7; slot [(rg*NB + nb)*4 + s][lane] is read back conflict-free ----
-        __syncthreads();   // the previous segment's merge buffers share this LDS
-        if (ts == 0) {
+        for (int i = 0; i < remaining;) {
+            // ---- a sequence starts (or continues from an earlier slice): its Q goes to this
+            //      wavefront's LDS, the accumulators restart ----
+            const int n_in = min(nt - kt, remaining - i);   // tiles of this sequence inside the slice
+            const bool first_of_slice = i == 0;
+            const int ctx = min(ctx_lens[b], p.max_pages * 16);
+            const int item_first_kt = kt;
+            f32x4 oacc[8][NB];
+            float mref[NB], lsum[NB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int row = rowbase + 16 * nb + n;
@@ -191,292 +246,194 @@ __global__ __launch_bounds__(256, (NB <= 2 ? 2 : 1)) void isd_attention_bf16_ker
                     const uint16_t* qp = p.q + ((size_t)(b * S + qpos[nb]) * p.Hq + kvh * G + gq) * 128;
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
-                        qlds[(nb * 4 + s) * 64 + lane] = *reinterpret_cast<const u32x4*>(qp + (4 * s + g) * 8);
+                        qlds[(nb * 4 + s) * 64] = *reinterpret_cast<const u32x4*>(qp + (4 * s + g) * 8);
                 } else {
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) qlds[(nb * 4 + s) * 64 + lane] = u32x4{0u, 0u, 0u, 0u};
+                    for (int s = 0; s < 4; ++s) qlds[(nb * 4 + s) * 64] = u32x4{0u, 0u, 0u, 0u};
                 }
+                mref[nb] = -INFINITY;
+                lsum[nb] = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) oacc[e][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-        }
-        __syncthreads();
+            int pb = b, pkt = kt, pnt = nt;   // cursor of the tile after this sequence's last one
 
-        f32x4 oacc[8][NB];
-        float mref[NB], lsum[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            mref[nb] = -INFINITY;
-            lsum[nb] = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) oacc[e][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-
-        const int32_t* __restrict__ tab = block_table + (size_t)b * p.max_pages;
-        const uint16_t* kh = p.k + kvh * p.head_stride;
-        const uint16_t* vh = p.v + kvh * p.head_stride;
-
-        // Page ids of tile kt (two 16-token pages).  The second id is only read when that page
-        // belongs to the sequence; otherwise the first page is read again and masked out.
-        auto page_ids = [&](int kt, int& pg0, int& pg1) {
-            const int pi = kt * 2;
-            pg0 = tab[pi];
-            pg1 = (pi + 1 < npages) ? tab[pi + 1] : pg0;
-        };
-        auto load_k = [&](int pg0, int pg1, KVTile& T_) {
-            const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride + n * p.token_stride + g * 8;
-            const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride + n * p.token_stride + g * 8;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                T_.k[0][s] = *reinterpret_cast<const bf16x8*>(k0 + 32 * s);
-                T_.k[1][s] = *reinterpret_cast<const bf16x8*>(k1 + 32 * s);
-            }
-        };
-        auto load_v = [&](int pg0, int pg1, KVTile& T_) {
-            const uint16_t* v0 = vh + (size_t)pg0 * p.page_stride + (4 * g) * p.token_stride + n * 8;
-            const uint16_t* v1 = vh + (size_t)pg1 * p.page_stride + (4 * g) * p.token_stride + n * 8;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                T_.v[j] = *reinterpret_cast<const u32x4*>(v0 + j * p.token_stride);
-                T_.v[4 + j] = *reinterpret_cast<const u32x4*>(v1 + j * p.token_stride);
-            }
-        };
-
-        // ---- main loop: this wavefront's tiles seg_a+ts, +TS, ...  One register image of a
-        //      tile; the next tile's K is requested as soon as St has consumed K, its V as soon
-        //      as Ot has consumed V, so loads stay in flight across the softmax and the other
-        //      contraction ----
-        KVTile T_;
-        int npg0 = 0, npg1 = 0;
-        if (seg_a + ts < seg_b) {
-            page_ids(seg_a + ts, npg0, npg1);
-            load_k(npg0, npg1, T_);
-            load_v(npg0, npg1, T_);
-            if (seg_a + ts + TS < seg_b) page_ids(seg_a + ts + TS, npg0, npg1);
-        }
-        for (int kt = seg_a + ts; kt < seg_b; kt += TS) {
-            const bool has_next = kt + TS < seg_b;
-            const int tb = 32 * kt;
-            // ---- St = K Qt ----
-            f32x4 sacc[NB][2];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                sacc[nb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-                sacc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const bf16x8 qb = __builtin_bit_cast(bf16x8, qlds[(nb * 4 + s) * 64 + lane]);
-                    sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T_.k[0][s], qb, sacc[nb][0], 0, 0, 0);
-                    sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(T_.k[1][s], qb, sacc[nb][1], 0, 0, 0);
-                }
-            if (has_next) load_k(npg0, npg1, T_);   // K registers are free again: next tile's K goes in flight
-            // ---- causal mask and end of context: only tiles that reach the stride's own rows ----
-            if (tb + 32 > ctx - S + 1) {
+            for (int t = 0; t < n_in; ++t, ++i) {
+                const int tb = 32 * (kt + t);
+                // ---- St = K Qt (Q operands are read back from LDS four registers at a time) ----
+                f32x4 sacc[NB][2];
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int lim = ctx - S + qpos[nb];   // last key this row may see
+                    sacc[nb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    sacc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const bf16x8 qb = __builtin_bit_cast(bf16x8, qlds[(nb * 4 + s) * 64]);
+                        sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][s], qb, sacc[nb][0], 0, 0, 0);
+                        sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][s], qb, sacc[nb][1], 0, 0, 0);
+                    }
+                load_k(npg0, npg1);   // K registers are free again: next tile's K goes in flight
+                // ---- causal mask and end of context: only tiles that reach the stride's own rows ----
+                if (tb + 32 > ctx - S + 1) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const int lim = ctx - S + qpos[nb];   // last key this row may see
+#pragma unroll
+                        for (int tblk = 0; tblk < 2; ++tblk)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (tb + 16 * tblk + 4 * g + j > lim) sacc[nb][tblk][j] = -INFINITY;
+                    }
+                    // value rows beyond the context may hold anything (NaN included): zero them
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj)
+                        if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) tv[jj] = u32x4{0u, 0u, 0u, 0u};
+                }
+                // ---- running reference exponent: rescale only when a score overshoots it ----
+                bool overshoot = false;
+                float lmax[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), fmaxf(sacc[nb][0][2], sacc[nb][0][3]));
+                    mx = fmaxf(mx, fmaxf(fmaxf(sacc[nb][1][0], sacc[nb][1][1]), fmaxf(sacc[nb][1][2], sacc[nb][1][3])));
+                    lmax[nb] = mx * cs;
+                    overshoot |= lmax[nb] > mref[nb] + kRescaleSlack;
+                }
+                if (__any(overshoot)) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        float rm = lmax[nb];
+                        rm = fmaxf(rm, __shfl_xor(rm, 16));
+                        rm = fmaxf(rm, __shfl_xor(rm, 32));
+                        const float mnew = fmaxf(mref[nb], rm);
+                        const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
+                        lsum[nb] *= alpha;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
+                        mref[nb] = mnew;
+                    }
+                }
+                // ---- Pt = 2^(St*scale - ref), packed straight into B-operand order ----
+                bf16x8 pt[NB];
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const float mr = (mref[nb] == -INFINITY) ? 0.f : mref[nb];
+                    float sum = 0.f;
 #pragma unroll
                     for (int tblk = 0; tblk < 2; ++tblk)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (tb + 16 * tblk + 4 * g + j > lim) sacc[nb][tblk][j] = -INFINITY;
+                        for (int j = 0; j < 4; ++j) {
+                            const float pv = fast_exp2(fmaf(sacc[nb][tblk][j], cs, -mr));
+                            sum += pv;
+                            pt[nb][4 * tblk + j] = (__bf16)pv;
+                        }
+                    lsum[nb] += sum;
                 }
-                // value rows beyond the context may hold anything (NaN included): zero them
+                // ---- Vt: transpose the lane's 8 tokens x 8 dims, then Ot += Vt Pt ----
 #pragma unroll
-                for (int jj = 0; jj < 8; ++jj)
-                    if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) T_.v[jj] = u32x4{0u, 0u, 0u, 0u};
-            }
-            // ---- running reference exponent: rescale only when a score overshoots it ----
-            bool overshoot = false;
-            float lmax[NB];
+                for (int e = 0; e < 8; ++e) {
+                    u32x4 vt;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), fmaxf(sacc[nb][0][2], sacc[nb][0][3]));
-                mx = fmaxf(mx, fmaxf(fmaxf(sacc[nb][1][0], sacc[nb][1][1]), fmaxf(sacc[nb][1][2], sacc[nb][1][3])));
-                lmax[nb] = mx * cs;
-                overshoot |= lmax[nb] > mref[nb] + kRescaleSlack;
+                    for (int wp = 0; wp < 4; ++wp) {
+                        const uint32_t x = tv[2 * wp][e >> 1], y = tv[2 * wp + 1][e >> 1];
+                        vt[wp] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+                    }
+                    const bf16x8 va = __builtin_bit_cast(bf16x8, vt);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        oacc[e][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[nb], oacc[e][nb], 0, 0, 0);
+                }
+                load_v(npg0, npg1);   // V registers are free again
+                // ---- cursors: c1 becomes the tile in flight's successor (scalar work only) ----
+                pb = c1b; pkt = c1kt; pnt = c1nt;
+                if (i + 2 < remaining) {
+                    advance(c1b, c1kt, c1nt);
+                    page_ids(c1b, c1kt, npg0, npg1);
+                }
             }
-            if (__any(overshoot)) {
+
+            // ---- the sequence (or the slice) ends here: write its rows ----
+            {
+                const bool complete = item_first_kt == 0 && kt + n_in == nt;
+                const size_t wslot = (size_t)(2 * wv + (first_of_slice ? 0 : 1)) * p.Mpad;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    float rm = lmax[nb];
-                    rm = fmaxf(rm, __shfl_xor(rm, 16));
-                    rm = fmaxf(rm, __shfl_xor(rm, 32));
-                    const float mnew = fmaxf(mref[nb], rm);
-                    const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
-                    lsum[nb] *= alpha;
+                    // denominators: add the four lanes (g = 0..3) that share a row
+                    float l = lsum[nb];
+                    l += __shfl_xor(l, 16);
+                    l += __shfl_xor(l, 32);
+                    const int row = rowbase + 16 * nb + n;
+                    if (row >= M) continue;
+                    // lane (row n, group g) holds dims 32g + 8j + e of its rows
+                    if (complete) {
+                        const float inv = 1.f / l;
+                        const int gq = row - qpos[nb] * G;
+                        uint16_t* op = p.out + ((size_t)(b * S + qpos[nb]) * p.Hq + kvh * G + gq) * 128 + 32 * g;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
-                    mref[nb] = mnew;
-                }
-            }
-            // ---- Pt = 2^(St*scale - ref), packed straight into B-operand order ----
-            bf16x8 pt[NB];
+                        for (int j = 0; j < 4; ++j) {
+                            bf16x8 o;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const float mr = (mref[nb] == -INFINITY) ? 0.f : mref[nb];
-                float sum = 0.f;
+                            for (int e = 0; e < 8; ++e) o[e] = (__bf16)(oacc[e][nb][j] * inv);
+                            *reinterpret_cast<bf16x8*>(op + 8 * j) = o;
+                        }
+                    } else {
+                        float* op = p.ws_o + (wslot + 16 * nb + n) * 128 + 32 * g;
 #pragma unroll
-                for (int tblk = 0; tblk < 2; ++tblk)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float pv = fast_exp2(fmaf(sacc[nb][tblk][j], cs, -mr));
-                        sum += pv;
-                        pt[nb][4 * tblk + j] = (__bf16)pv;
-                    }
-                lsum[nb] += sum;
-            }
-            // ---- Vt: transpose the lane's 8 tokens x 8 dims, then Ot += Vt Pt ----
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                u32x4 vt;
-#pragma unroll
-                for (int wp = 0; wp < 4; ++wp) {
-                    const uint32_t x = T_.v[2 * wp][e >> 1], y = T_.v[2 * wp + 1][e >> 1];
-                    vt[wp] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-                }
-                const bf16x8 va = __builtin_bit_cast(bf16x8, vt);
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    oacc[e][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[nb], oacc[e][nb], 0, 0, 0);
-            }
-            if (has_next) {
-                load_v(npg0, npg1, T_);                  // V registers are free again
-                if (kt + 2 * TS < seg_b) page_ids(kt + 2 * TS, npg0, npg1);
-            }
-        }
-
-        // denominators: add the four lanes (g = 0..3) that share a row
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            lsum[nb] += __shfl_xor(lsum[nb], 16);
-            lsum[nb] += __shfl_xor(lsum[nb], 32);
-        }
-
-        // ---- merge the TS wavefronts of a row group through LDS (same register layout on both sides) ----
-        auto spill = [&](int slot) {
-            float* dst = lds + (size_t)slot * NREG * 64 + lane;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) dst[((nb * 8 + e) * 4 + j) * 64] = oacc[e][nb][j];
-                dst[(32 * NB + 2 * nb) * 64] = mref[nb];
-                dst[(32 * NB + 2 * nb + 1) * 64] = lsum[nb];
-            }
-        };
-        auto absorb = [&](int slot) {
-            const float* src = lds + (size_t)slot * NREG * 64 + lane;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const float m2 = src[(32 * NB + 2 * nb) * 64];
-                const float l2 = src[(32 * NB + 2 * nb + 1) * 64];
-                const float mnew = fmaxf(mref[nb], m2);
-                const float a1 = (mref[nb] == -INFINITY) ? 0.f : fast_exp2(mref[nb] - mnew);
-                const float a2 = (m2 == -INFINITY) ? 0.f : fast_exp2(m2 - mnew);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        oacc[e][nb][j] = oacc[e][nb][j] * a1 + src[((nb * 8 + e) * 4 + j) * 64] * a2;
-                lsum[nb] = lsum[nb] * a1 + l2 * a2;
-                mref[nb] = mnew;
-            }
-        };
-        if constexpr (TS > 1) __syncthreads();   // every wavefront is done with Q: its LDS is reused below
-        if constexpr (TS == 4) {
-            if (ts >= 2) spill(ts - 2);
-            __syncthreads();
-            if (ts < 2) absorb(ts);
-            __syncthreads();
-            if (ts == 1) spill(0);
-            __syncthreads();
-            if (ts == 0) absorb(0);
-        } else if constexpr (TS == 2) {
-            if (ts == 1) spill(rg);
-            __syncthreads();
-            if (ts == 0) absorb(rg);
-        }
-
-        // ---- write: lane (row n, group g) holds dims 32g + 8j + e of its rows ----
-        if (ts == 0) {
-            const size_t wslot = (size_t)(2 * wg + (first_segment ? 0 : 1)) * p.Mpad;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int row = rowbase + 16 * nb + n;
-                if (row >= M) continue;
-                if (complete) {
-                    const float inv = 1.f / lsum[nb];
-                    const int i = qpos[nb], gq = row - i * G;
-                    uint16_t* op = p.out + ((size_t)(b * S + i) * p.Hq + kvh * G + gq) * 128 + 32 * g;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        bf16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(oacc[e][nb][j] * inv);
-                        *reinterpret_cast<bf16x8*>(op + 8 * j) = o;
-                    }
-                } else {
-                    float* op = p.ws_o + (wslot + row) * 128 + 32 * g;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        *reinterpret_cast<f32x4*>(op + 8 * j) = f32x4{oacc[0][nb][j], oacc[1][nb][j], oacc[2][nb][j], oacc[3][nb][j]};
-                        *reinterpret_cast<f32x4*>(op + 8 * j + 4) = f32x4{oacc[4][nb][j], oacc[5][nb][j], oacc[6][nb][j], oacc[7][nb][j]};
-                    }
-                    if (g == 0) {
-                        p.ws_ml[(wslot + row) * 2] = mref[nb];
-                        p.ws_ml[(wslot + row) * 2 + 1] = lsum[nb];
+                        for (int j = 0; j < 4; ++j) {
+                            *reinterpret_cast<f32x4*>(op + 8 * j) = f32x4{oacc[0][nb][j], oacc[1][nb][j], oacc[2][nb][j], oacc[3][nb][j]};
+                            *reinterpret_cast<f32x4*>(op + 8 * j + 4) = f32x4{oacc[4][nb][j], oacc[5][nb][j], oacc[6][nb][j], oacc[7][nb][j]};
+                        }
+                        if (g == 0) {
+                            p.ws_ml[(wslot + 16 * nb + n) * 2] = mref[nb];
+                            p.ws_ml[(wslot + 16 * nb + n) * 2 + 1] = l;
+                        }
                     }
                 }
             }
-        }
-
-        // ---- next segment: the next non-empty sequence ----
-        pos += seg_b - seg_a;
-        first_segment = false;
-        seg_a = 0;
-        if (pos < slice_end) {
-            do { ++b; ntiles = seq_tiles(p, ctx_lens, b); } while (ntiles == 0);
+            b = pb; kt = pkt; nt = pnt;   // first tile of the next sequence (unused after the last one)
         }
     }
-    }   // heads
 }
 
-// Joins the partials of items that span several workgroups.  Block (h, j) looks at the cut
-// between slices j-1 and j of head h's tile list (the main kernel's partition); the block of the
-// first cut that falls inside an item merges all of that item's partials:
+// Joins the partials of sequences that span several wavefront slices.  Block (vh, j) looks at the
+// cut between slices j-1 and j of virtual head vh (the main kernel's partition); the block of the
+// first cut that falls inside a sequence merges all of that sequence's partials:
 // out = sum_k 2^(m_k - m*) O_k / sum_k 2^(m_k - m*) l_k.
-__global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnParams p, int Wg,
+__global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnParams p, int Wg, int rows_per_group,
                                                                   const int32_t* __restrict__ ctx_lens)
 {
     __shared__ TilePlan plan;
     const int total = plan_scan(p, ctx_lens, plan);
-    const int kvh = blockIdx.x % p.Hkv;
-    const int jcut = blockIdx.x / p.Hkv + 1;       // cut = start of slice jcut
-    const int cut = (int)((int64_t)total * jcut / Wg);
+    if (total == 0) return;
+    const int VH = p.Hkv * p.RG;
+    const int vh = blockIdx.x % VH;
+    const int jcut = blockIdx.x / VH + 1;          // cut = start of slice jcut
+    auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
+    const int cut = slice_start(jcut);
     if (cut <= 0 || cut >= total) return;
     int b, pre;
     plan_locate(p, ctx_lens, plan, cut, b, pre);
     const int ntiles = seq_tiles(p, ctx_lens, b);
-    const int a = cut - pre;
-    if (a == 0) return;                            // the cut coincides with the start of an item
+    if (cut == pre) return;                        // the cut coincides with the start of a sequence
     const int item_begin = pre, item_end = pre + ntiles;
-    auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
-    if (slice_start(jcut - 1) > item_begin) return;   // an earlier cut is inside the same item
-    // slices jcut-1 .. hold this item's partials, written by workgroup j*Hkv + kvh into slot 2w if
-    // the item is the first segment of that slice (the slice starts inside the item), 2w+1 if it
-    // is its last
-    auto slot_of = [&](int j, int jbeg) { return 2 * (j * p.Hkv + kvh) + (jbeg >= item_begin ? 0 : 1); };
-    for (int idx = threadIdx.x; idx < p.M * 32; idx += 256) {
-        const int row = idx >> 5, d4 = idx & 31;
+    if (slice_start(jcut - 1) > item_begin) return;   // an earlier cut is inside the same sequence
+    // slices jcut-1 .. hold this sequence's partials, written by wavefront j*VH + vh into slot 2v if
+    // the sequence is the first one of that slice (the slice starts inside it), 2v+1 if it is its last
+    auto slot_of = [&](int j, int jbeg) { return 2 * (j * VH + vh) + (jbeg >= item_begin ? 0 : 1); };
+    const int kvh = vh / p.RG;
+    const int rowbase = (vh - kvh * p.RG) * rows_per_group;
+    const int nrows = min(rows_per_group, p.M - rowbase);
+    for (int idx = threadIdx.x; idx < nrows * 32; idx += 256) {
+        const int lrow = idx >> 5, d4 = idx & 31;
         float mstar = -INFINITY;
         for (int j = jcut - 1; j < Wg; ++j) {
             const int jbeg = slice_start(j), jend = slice_start(j + 1);
             if (jbeg >= item_end) break;
             if (jbeg == jend) continue;
-            mstar = fmaxf(mstar, p.ws_ml[((size_t)slot_of(j, jbeg) * p.Mpad + row) * 2]);
+            mstar = fmaxf(mstar, p.ws_ml[((size_t)slot_of(j, jbeg) * p.Mpad + lrow) * 2]);
         }
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         float den = 0.f;
@@ -484,13 +441,14 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
             const int jbeg = slice_start(j), jend = slice_start(j + 1);
             if (jbeg >= item_end) break;
             if (jbeg == jend) continue;
-            const size_t s = (size_t)slot_of(j, jbeg) * p.Mpad + row;
+            const size_t s = (size_t)slot_of(j, jbeg) * p.Mpad + lrow;
             const float m = p.ws_ml[s * 2];
             const float wgt = (m == -INFINITY) ? 0.f : fast_exp2(m - mstar);
             den += wgt * p.ws_ml[s * 2 + 1];
             acc += *reinterpret_cast<const f32x4*>(p.ws_o + s * 128 + d4 * 4) * wgt;
         }
         const float inv = 1.f / den;
+        const int row = rowbase + lrow;
         const int i = row / p.G, gq = row - i * p.G;
         uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + d4 * 4;
         bf16x4 o4;
@@ -595,15 +553,12 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
     return true;
 }
 
+// 16-row blocks per wavefront (NB) and groups of 16*NB rows per KV head (RG) for M = S*G query rows
 static void row_tiling(int M, int* NB, int* RG)
 {
     if (M <= 16) { *NB = 1; *RG = 1; }
     else if (M <= 32) { *NB = 2; *RG = 1; }
-#ifdef IDLM_EXP_M64_22
-    else if (M <= 64) { *NB = 2; *RG = 2; }
-#else
     else if (M <= 64) { *NB = 4; *RG = 1; }
-#endif
     else if (M <= 128) { *NB = 4; *RG = 2; }
     else { *NB = 4; *RG = 4; }
 }
@@ -620,7 +575,8 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
     if (dtype != IDLM_DTYPE_BF16 || B == 0) return 0;
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
-    const size_t rows = (size_t)2 * kMaxWorkgroups * (16 * NB * RG);
+    // two partial slots of 16*NB rows per wavefront of the largest grid
+    const size_t rows = (size_t)2 * kMaxWorkgroups * 4 * (16 * NB);
     return rows * 128 * sizeof(float) + rows * 2 * sizeof(float);
 }
 
@@ -688,10 +644,10 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.v = static_cast<const uint16_t*>(v_cache);
     p.out = static_cast<uint16_t*>(out);
     p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.M = S * G; p.max_pages = max_pages_per_seq;
-    int NB, RG;
-    row_tiling(p.M, &NB, &RG);
-    p.Mpad = 16 * NB * RG;
-    const size_t rows = (size_t)2 * kMaxWorkgroups * p.Mpad;
+    int NB;
+    row_tiling(p.M, &NB, &p.RG);
+    p.Mpad = 16 * NB;
+    const size_t rows = (size_t)2 * kMaxWorkgroups * 4 * p.Mpad;
     p.ws_o = static_cast<float*>(workspace);
     p.ws_ml = p.ws_o + rows * 128;
     p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
@@ -699,29 +655,19 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
 
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
-    const int nreg = 32 * NB + 2 * NB;
-#define IDLM_LAUNCH_ATTN(NB_, RG_, SLOTS_)                                                              \
-    do {                                                                                                 \
-        size_t shmem = (size_t)(SLOTS_) * nreg * 64 * sizeof(float);                                     \
-        const size_t qbytes = (size_t)(RG_) * (NB_) * 4 * 64 * 16;                                       \
-        if (qbytes > shmem) shmem = qbytes;                                                              \
-        if (shmem > 65536 - sizeof(TilePlan))                                                            \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<NB_, RG_>), \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);           \
-        hipLaunchKernelGGL((isd_attention_bf16_kernel<NB_, RG_>), dim3(W), dim3(256), shmem, st, p,      \
-                           block_table, ctx_lens);                                                      \
-    } while (0)
-    if (NB == 1) IDLM_LAUNCH_ATTN(1, 1, 2);
-    else if (NB == 2 && RG == 1) IDLM_LAUNCH_ATTN(2, 1, 2);
-    else if (NB == 2) IDLM_LAUNCH_ATTN(2, 2, 2);
-    else if (RG == 1) IDLM_LAUNCH_ATTN(4, 1, 2);
-    else if (RG == 2) IDLM_LAUNCH_ATTN(4, 2, 2);
-    else IDLM_LAUNCH_ATTN(4, 4, 0);
-#undef IDLM_LAUNCH_ATTN
+    const size_t shmem = (size_t)4 * NB * 4 * 64 * 16;   // Q operands of the four wavefronts' current sequences
+    if (NB == 4)   // 64 KB of Q operands plus the static plan exceed the default 64 KB limit
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (NB == 1) hipLaunchKernelGGL(isd_attention_bf16_kernel<1>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
+    else if (NB == 2) hipLaunchKernelGGL(isd_attention_bf16_kernel<2>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
+    else hipLaunchKernelGGL(isd_attention_bf16_kernel<4>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
-    const int Wg = W >= Hkv ? W / Hkv : 1;   // slices per head, as in the main kernel
+    const int VH = Hkv * p.RG, NW = W * 4;
+    const int Wg = NW >= VH ? NW / VH : 1;   // slices per virtual head, as in the main kernel
     if (Wg > 1)
-        hipLaunchKernelGGL(isd_attention_merge_kernel, dim3((unsigned)((Wg - 1) * Hkv)), dim3(256), 0, st, p, Wg, ctx_lens);
+        hipLaunchKernelGGL(isd_attention_merge_kernel, dim3((unsigned)((Wg - 1) * VH)), dim3(256), 0, st, p, Wg,
+                           p.Mpad, ctx_lens);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
 }
