@@ -1,7 +1,6 @@
 // Error strings, version, and two plain streaming kernels used to calibrate byte counters and
 // to measure the bandwidth a pure copy / pure read reaches on the device.
 #include "idlm_common.h"
-#include <stdlib.h>
 
 namespace idlm {
 
@@ -76,12 +75,7 @@ extern "C" int idlm_stream_read(const void* src, size_t n_bytes, uint32_t* sink,
     const size_t blocks = (n16 + 4095) / 4096;
     if (blocks > 0x7fffffffu) return IDLM_ERR_SHAPE;
     (void)hipGetLastError();
-    size_t exp_lds = 0;
-    if (const char* e = getenv("IDLM_EXP_LDS")) {
-        exp_lds = (size_t)atol(e);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_read_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)exp_lds);
-    }
-    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), exp_lds, static_cast<hipStream_t>(stream),
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4*>(src), n16, sink);
     return launch_status();
 }

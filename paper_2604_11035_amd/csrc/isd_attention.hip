@@ -41,8 +41,8 @@ struct AttnParams {
     const uint16_t* k;
     const uint16_t* v;
     uint16_t* out;
-    float* ws_o;    // [2*NW][Mpad][128] unnormalised partial outputs (slot 2v: first sequence of
-    float* ws_ml;   // [2*NW][Mpad][2]   wavefront v's slice, 2v+1: its last) and (reference exponent, denominator)
+    float* ws_o;    // [2*NW][NB][8][64][4] unnormalised partial outputs, accumulator registers as they are (slot 2v: first
+    float* ws_ml;   // [2*NW][NB][16][2]    sequence of wavefront v's slice, 2v+1: its last); (reference exponent, denominator)
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
@@ -60,6 +60,23 @@ struct TilePlan {     // static LDS of both kernels
     int found_b;      // sequence that holds a looked-up position ...
     int found_pre;    // ... and the number of tiles (one head) before it
 };
+
+// Copies one accumulation register to an ordinary vector register at exactly this point of the
+// program (the compiler neither hoists nor batches it).
+__device__ __forceinline__ float acc_read(float a)
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// The value of x, hidden from the optimiser: what is computed from it is computed here and now
+// instead of once, ahead of the loops, and then kept in (or spilled from) a register.
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
 
 // 32-token tiles of sequence b (for one KV head).  A context longer than the block table can
 // describe is a broken precondition; the table is never walked past its end.
@@ -195,22 +212,26 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         };
         bf16x8 tk[2][4];   // K of the current tile: [16-token block][k-step], A operand of St
         u32x4 tv[8];       // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
+        // Addresses are a wave-uniform 64-bit page base plus a 32-bit lane offset (the host checks that
+        // the offset fits): one address register per lane instead of a 64-bit pair per page.
+        const uint32_t klane = (uint32_t)(n * (int)p.token_stride + g * 8);
+        const uint32_t vlane = (uint32_t)(4 * g * (int)p.token_stride + n * 8);
         auto load_k = [&](int pg0, int pg1) {
-            const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride + n * p.token_stride + g * 8;
-            const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride + n * p.token_stride + g * 8;
+            const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride;
+            const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                tk[0][s] = *reinterpret_cast<const bf16x8*>(k0 + 32 * s);
-                tk[1][s] = *reinterpret_cast<const bf16x8*>(k1 + 32 * s);
+                tk[0][s] = *reinterpret_cast<const bf16x8*>(k0 + klane + 32 * s);
+                tk[1][s] = *reinterpret_cast<const bf16x8*>(k1 + klane + 32 * s);
             }
         };
         auto load_v = [&](int pg0, int pg1) {
-            const uint16_t* v0 = vhp + (size_t)pg0 * p.page_stride + (4 * g) * p.token_stride + n * 8;
-            const uint16_t* v1 = vhp + (size_t)pg1 * p.page_stride + (4 * g) * p.token_stride + n * 8;
+            const uint16_t* v0 = vhp + (size_t)pg0 * p.page_stride;
+            const uint16_t* v1 = vhp + (size_t)pg1 * p.page_stride;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tv[j] = *reinterpret_cast<const u32x4*>(v0 + j * p.token_stride);
-                tv[4 + j] = *reinterpret_cast<const u32x4*>(v1 + j * p.token_stride);
+                tv[j] = *reinterpret_cast<const u32x4*>(v0 + j * p.token_stride + vlane);
+                tv[4 + j] = *reinterpret_cast<const u32x4*>(v1 + j * p.token_stride + vlane);
             }
         };
 
@@ -229,9 +250,34 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             page_ids(c1b, c1kt, npg0, npg1);
         }
 
+        // Q rows of sequence bq for this lane (row n of each 16-row block, dims 32s + 8g .. +7); rows
+        // past the stride's last one read its last row instead and are zeroed on the way to LDS
+        u32x4 qreg[NB][4];
+        auto load_q = [&](int bq) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int row = opaque(rowbase + 16 * nb + n);
+                const int qi = row < M ? qpos[nb] : S - 1;
+                const int gq = row < M ? row - qpos[nb] * G : G - 1;
+                const uint16_t* qp = p.q + ((size_t)(bq * S + qi) * p.Hq + kvh * G + gq) * 128 + g * 8;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) qreg[nb][s] = *reinterpret_cast<const u32x4*>(qp + 32 * s);
+            }
+        };
+        auto store_q = [&]() {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const bool valid = opaque(rowbase + 16 * nb + n) < M;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) qlds[(nb * 4 + s) * 64] = valid ? qreg[nb][s] : u32x4{0u, 0u, 0u, 0u};
+            }
+        };
+        load_q(b);
+        store_q();
+
         for (int i = 0; i < remaining;) {
-            // ---- a sequence starts (or continues from an earlier slice): its Q goes to this
-            //      wavefront's LDS, the accumulators restart ----
+            // ---- a sequence starts (or continues from an earlier slice); its Q is in this wavefront's
+            //      LDS already, the accumulators restart ----
             const int n_in = min(nt - kt, remaining - i);   // tiles of this sequence inside the slice
             const bool first_of_slice = i == 0;
             const int ctx = min(ctx_lens[b], p.max_pages * 16);
@@ -240,17 +286,6 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             float mref[NB], lsum[NB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const int row = rowbase + 16 * nb + n;
-                if (row < M) {
-                    const int gq = row - qpos[nb] * G;
-                    const uint16_t* qp = p.q + ((size_t)(b * S + qpos[nb]) * p.Hq + kvh * G + gq) * 128;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-                        qlds[(nb * 4 + s) * 64] = *reinterpret_cast<const u32x4*>(qp + (4 * s + g) * 8);
-                } else {
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) qlds[(nb * 4 + s) * 64] = u32x4{0u, 0u, 0u, 0u};
-                }
                 mref[nb] = -INFINITY;
                 lsum[nb] = 0.f;
 #pragma unroll
@@ -355,44 +390,84 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 }
             }
 
-            // ---- the sequence (or the slice) ends here: write its rows ----
+            // ---- the sequence (or the slice) ends here.  The next sequence's Q is requested first:
+            //      the memory counter retires in order, so Q can then be waited for without waiting
+            //      for the acknowledgement of the stores below (after the last sequence the request
+            //      repeats the current Q: unconditional requests keep the outstanding count exact). ----
+            load_q(i < remaining ? pb : b);
             {
                 const bool complete = item_first_kt == 0 && kt + n_in == nt;
-                const size_t wslot = (size_t)(2 * wv + (first_of_slice ? 0 : 1)) * p.Mpad;
+                const size_t wslot = (size_t)(2 * wv + (first_of_slice ? 0 : 1));
+                const int q4 = n & 3;
+                // The accumulators sit in accumulation registers, which vector ALU instructions cannot
+                // read; they are copied out sixteen-row block by block right where they are used
+                // (left to itself the compiler copies all of them out at once and then runs out of
+                // registers, and the reloads of what it spilled drain the memory counter between the
+                // stores).  An MFMA result needs up to 18 idle cycles before such a copy may read it.
+                asm volatile("s_nop 15\n\ts_nop 15");
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     // denominators: add the four lanes (g = 0..3) that share a row
                     float l = lsum[nb];
                     l += __shfl_xor(l, 16);
                     l += __shfl_xor(l, 32);
-                    const int row = rowbase + 16 * nb + n;
-                    if (row >= M) continue;
-                    // lane (row n, group g) holds dims 32g + 8j + e of its rows
                     if (complete) {
+                        // Every store instruction should write whole 128-byte lines.  Lane (row n, group
+                        // g) holds dims 32g + 8j + e as four 16-byte chunks j.  A 4x4 transpose between
+                        // j and the four lanes of a quad leaves lane (n, g) with chunk 4g + n%4 of rows
+                        // 4*(n/4) + j: store j then writes four complete 256-byte rows.
                         const float inv = 1.f / l;
-                        const int gq = row - qpos[nb] * G;
-                        uint16_t* op = p.out + ((size_t)(b * S + qpos[nb]) * p.Hq + kvh * G + gq) * 128 + 32 * g;
+                        u32x4 c[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             bf16x8 o;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) o[e] = (__bf16)(oacc[e][nb][j] * inv);
-                            *reinterpret_cast<bf16x8*>(op + 8 * j) = o;
+                            for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc_read(oacc[e][nb][j]) * inv);
+                            c[j] = __builtin_bit_cast(u32x4, o);
                         }
-                    } else {
-                        float* op = p.ws_o + (wslot + 16 * nb + n) * 128 + 32 * g;
+#pragma unroll
+                        for (int stage = 1; stage <= 2; ++stage) {
+                            const bool hi = (q4 & stage) != 0;
+#pragma unroll
+                            for (int pair = 0; pair < 2; ++pair) {
+                                // stage 1 swaps chunks (0,1) and (2,3) with lane^1, stage 2 (0,2) and (1,3) with lane^2
+                                const int lo_i = stage == 1 ? 2 * pair : pair, hi_i = lo_i + stage;
+                                u32x4 send, recv;
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) send[k] = hi ? c[lo_i][k] : c[hi_i][k];
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) recv[k] = __shfl_xor(send[k], stage);
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) {
+                                    if (hi) c[lo_i][k] = recv[k]; else c[hi_i][k] = recv[k];
+                                }
+                            }
+                        }
+                        const int row0 = opaque(rowbase + 16 * nb + (n & 12));
+                        int ip = row0 / G, gq = row0 - ip * G;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            *reinterpret_cast<f32x4*>(op + 8 * j) = f32x4{oacc[0][nb][j], oacc[1][nb][j], oacc[2][nb][j], oacc[3][nb][j]};
-                            *reinterpret_cast<f32x4*>(op + 8 * j + 4) = f32x4{oacc[4][nb][j], oacc[5][nb][j], oacc[6][nb][j], oacc[7][nb][j]};
+                            if (row0 + j < M) {
+                                uint16_t* op = p.out + ((size_t)(b * S + ip) * p.Hq + kvh * G + gq) * 128 + (4 * g + q4) * 8;
+                                *reinterpret_cast<u32x4*>(op) = c[j];
+                            }
+                            if (++gq == G) { gq = 0; ++ip; }
                         }
+                    } else {
+                        // partial: the accumulators as they are, [nb][e][lane] quads (j = 0..3) = dims
+                        // 32g + 8j + e of local row 16nb + n; 1 KB per store instruction
+                        float* op = p.ws_o + ((wslot * NB + nb) * 8 * 64 + lane) * 4;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) *reinterpret_cast<f32x4*>(op + e * 256) = oacc[e][nb];
                         if (g == 0) {
-                            p.ws_ml[(wslot + 16 * nb + n) * 2] = mref[nb];
-                            p.ws_ml[(wslot + 16 * nb + n) * 2 + 1] = l;
+                            float* mp = p.ws_ml + ((wslot * NB + nb) * 16 + n) * 2;
+                            mp[0] = mref[nb];
+                            mp[1] = l;
                         }
                     }
                 }
             }
+            store_q();
             b = pb; kt = pkt; nt = pnt;   // first tile of the next sequence (unused after the last one)
         }
     }
@@ -426,35 +501,46 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int kvh = vh / p.RG;
     const int rowbase = (vh - kvh * p.RG) * rows_per_group;
     const int nrows = min(rows_per_group, p.M - rowbase);
-    for (int idx = threadIdx.x; idx < nrows * 32; idx += 256) {
-        const int lrow = idx >> 5, d4 = idx & 31;
+    // partial layout: [slot][nb][e][lane = 16g+n][j] floats = dim 32g + 8j + e of local row
+    // 16nb + n; (reference exponent, denominator) at [slot][nb][n].  Thread (nb, lane, j) gathers
+    // e = 0..7: reads are contiguous across threads, and its eight dims are one 16-byte store.
+    const int NBk = rows_per_group >> 4;
+    for (int idx = threadIdx.x; idx < NBk * 256; idx += 256) {
+        const int j = idx & 3, lane = (idx >> 2) & 63, nb = idx >> 8;
+        const int n = lane & 15, g = lane >> 4;
+        const int lrow = 16 * nb + n;
+        if (lrow >= nrows) continue;
         float mstar = -INFINITY;
-        for (int j = jcut - 1; j < Wg; ++j) {
-            const int jbeg = slice_start(j), jend = slice_start(j + 1);
-            if (jbeg >= item_end) break;
-            if (jbeg == jend) continue;
-            mstar = fmaxf(mstar, p.ws_ml[((size_t)slot_of(j, jbeg) * p.Mpad + lrow) * 2]);
+        for (int k = jcut - 1; k < Wg; ++k) {
+            const int kbeg = slice_start(k), kend = slice_start(k + 1);
+            if (kbeg >= item_end) break;
+            if (kbeg == kend) continue;
+            mstar = fmaxf(mstar, p.ws_ml[(((size_t)slot_of(k, kbeg) * NBk + nb) * 16 + n) * 2]);
         }
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
         float den = 0.f;
-        for (int j = jcut - 1; j < Wg; ++j) {
-            const int jbeg = slice_start(j), jend = slice_start(j + 1);
-            if (jbeg >= item_end) break;
-            if (jbeg == jend) continue;
-            const size_t s = (size_t)slot_of(j, jbeg) * p.Mpad + lrow;
-            const float m = p.ws_ml[s * 2];
+        for (int k = jcut - 1; k < Wg; ++k) {
+            const int kbeg = slice_start(k), kend = slice_start(k + 1);
+            if (kbeg >= item_end) break;
+            if (kbeg == kend) continue;
+            const size_t sl = (size_t)slot_of(k, kbeg) * NBk + nb;
+            const float m = p.ws_ml[(sl * 16 + n) * 2];
             const float wgt = (m == -INFINITY) ? 0.f : fast_exp2(m - mstar);
-            den += wgt * p.ws_ml[s * 2 + 1];
-            acc += *reinterpret_cast<const f32x4*>(p.ws_o + s * 128 + d4 * 4) * wgt;
+            den += wgt * p.ws_ml[(sl * 16 + n) * 2 + 1];
+            const float* src = p.ws_o + (sl * 8 * 64 + lane) * 4 + j;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += src[e * 256] * wgt;
         }
         const float inv = 1.f / den;
         const int row = rowbase + lrow;
         const int i = row / p.G, gq = row - i * p.G;
-        uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + d4 * 4;
-        bf16x4 o4;
+        bf16x8 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(acc[e] * inv);
-        *reinterpret_cast<bf16x4*>(op) = o4;
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
+        uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + 32 * g + 8 * j;
+        *reinterpret_cast<bf16x8*>(op) = o;
     }
 }
 
@@ -591,6 +677,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     int err;
     if (!shapes_ok(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, &err)) return err;
     if (num_pages < 1 || page_stride < 1 || head_stride < 1 || token_stride < D) return IDLM_ERR_SHAPE;
+    if (token_stride > (1 << 24)) return IDLM_ERR_SHAPE;   // lane offsets inside a page are 32-bit
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return IDLM_ERR_SHAPE;
     if (B == 0) return IDLM_OK;
     if (!q || !k_cache || !v_cache || !block_table || !ctx_lens || !out) return IDLM_ERR_NULL;
