@@ -57,8 +57,7 @@ constexpr float kRescaleSlack = 12.0f;
 
 struct TilePlan {     // static LDS of both kernels
     int incl[256];    // inclusive prefix sums of the per-thread tile counts
-    int found_b;      // sequence that holds a looked-up position ...
-    int found_pre;    // ... and the number of tiles (one head) before it
+    int wave_sum[4];  // tiles counted by each of the block's four wavefronts
 };
 
 // Copies one accumulation register to an ordinary vector register at exactly this point of the
@@ -86,52 +85,69 @@ __device__ __forceinline__ int seq_tiles(const AttnParams& p, const int32_t* __r
     return c > 0 ? (c + 31) >> 5 : 0;
 }
 
-// Block-wide inclusive scan of tile counts (thread t sums sequences [t*per, (t+1)*per)).
+// Block-wide inclusive scan of tile counts (thread t sums sequences [t*per, (t+1)*per)): a shuffle
+// scan inside each wavefront, then the wavefront totals through LDS - two barriers in all.
 // Returns the total number of tiles of one head.  Every thread of the block must call it.
 __device__ __forceinline__ int plan_scan(const AttnParams& p, const int32_t* __restrict__ ctx_lens, TilePlan& plan)
 {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int per = (p.B + 255) >> 8;
     const int b0 = tid * per, b1 = min(p.B, b0 + per);
-    int local = 0;
-    for (int b = b0; b < b1; ++b) local += seq_tiles(p, ctx_lens, b);
-    plan.incl[tid] = local;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        const int add = (tid >= off) ? plan.incl[tid - off] : 0;
-        __syncthreads();
-        plan.incl[tid] += add;
-        __syncthreads();
+    int x = 0;
+    for (int b = b0; b < b1; ++b) x += seq_tiles(p, ctx_lens, b);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(x, off);
+        if (lane >= off) x += y;
     }
-    return __builtin_amdgcn_readfirstlane(plan.incl[255]);   // wave-uniform: keep it in a scalar register
+    if (lane == 63) plan.wave_sum[w] = x;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int sk = plan.wave_sum[k];
+        before += (k < w) ? sk : 0;
+        total += sk;
+    }
+    plan.incl[tid] = x + before;
+    __syncthreads();
+    return __builtin_amdgcn_readfirstlane(total);   // wave-uniform: keep it in a scalar register
 }
 
-// Sequence b that holds per-head tile position x (0 <= x < total) and the tiles before it.
-// Every thread of the block must call it (after plan_scan).
-__device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* __restrict__ ctx_lens, TilePlan& plan,
+// Sequence b that holds per-head tile position x (0 <= x < total) and the tiles before it.  A
+// wavefront-level lookup (after plan_scan): x must be the same in all lanes of the calling
+// wavefront, different wavefronts may look up different positions, nobody waits for anybody.
+__device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* __restrict__ ctx_lens, const TilePlan& plan,
                                             int x, int& b, int& pre)
 {
-    const int tid = threadIdx.x;
-    const int incl = plan.incl[tid];
-    const int excl = tid ? plan.incl[tid - 1] : 0;
-    if (excl <= x && x < incl) {
-        const int per = (p.B + 255) >> 8;
-        int bb = tid * per, acc = excl;
-        for (;;) {
-            const int nt = seq_tiles(p, ctx_lens, bb);
-            if (x < acc + nt) break;
-            acc += nt;
-            ++bb;
+    const int lane = threadIdx.x & 63;
+    int fb = 0, fpre = 0;
+    bool found = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int t = lane + 64 * k;
+        const int incl = plan.incl[t];
+        const int excl = t ? plan.incl[t - 1] : 0;
+        if (excl <= x && x < incl) {     // true for exactly one t of the 256
+            const int per = (p.B + 255) >> 8;
+            int bb = t * per, acc = excl;
+            for (;;) {
+                const int nt = seq_tiles(p, ctx_lens, bb);
+                if (x < acc + nt) break;
+                acc += nt;
+                ++bb;
+            }
+            fb = bb;
+            fpre = acc;
+            found = true;
         }
-        plan.found_b = bb;
-        plan.found_pre = acc;
     }
-    __syncthreads();
     // the same value in every lane: scalar registers, so that everything derived from it
     // (table pointer, page ids, loop bounds) stays on the scalar unit
-    b = __builtin_amdgcn_readfirstlane(plan.found_b);
-    pre = __builtin_amdgcn_readfirstlane(plan.found_pre);
-    __syncthreads();
+    const unsigned long long mask = __ballot(found);
+    const int src = __builtin_amdgcn_readfirstlane((int)__ffsll((long long)mask) - 1);
+    b = __builtin_amdgcn_readlane(fb, src);
+    pre = __builtin_amdgcn_readlane(fpre, src);
 }
 
 // The block table and the context lengths are separate __restrict__ kernel arguments: nothing
@@ -163,21 +179,13 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     auto slice_of = [&](int v) { return NW >= VH ? v / VH : 0; };
     auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
 
-    // first sequence of every wavefront's slice (the lookup is block-wide: all four take part)
     const int wv = blockIdx.x * 4 + w;
-    int b0 = 0, pre0 = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int jk = slice_of(blockIdx.x * 4 + k);
-        const int xk = (jk < Wg) ? slice_start(jk) : 0;
-        int bk, prek;
-        plan_locate(p, ctx_lens, plan, min(xk, total - 1), bk, prek);
-        if (k == w) { b0 = bk; pre0 = prek; }
-    }
     const int slice = slice_of(wv);
     if (slice >= Wg) return;
     const int slice_begin = slice_start(slice), slice_end = slice_start(slice + 1);
     if (slice_begin >= slice_end) return;
+    int b0, pre0;   // first sequence of the slice and the tiles before it
+    plan_locate(p, ctx_lens, plan, slice_begin, b0, pre0);
     const int vh0 = NW >= VH ? wv % VH : wv;
     const int vstep = NW >= VH ? VH : NW;
 
@@ -502,45 +510,63 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int rowbase = (vh - kvh * p.RG) * rows_per_group;
     const int nrows = min(rows_per_group, p.M - rowbase);
     // partial layout: [slot][nb][e][lane = 16g+n][j] floats = dim 32g + 8j + e of local row
-    // 16nb + n; (reference exponent, denominator) at [slot][nb][n].  Thread (nb, lane, j) gathers
-    // e = 0..7: reads are contiguous across threads, and its eight dims are one 16-byte store.
+    // 16nb + n; (reference exponent, denominator) at [slot][nb][n].  Thread (lane, j) gathers
+    // e = 0..7 of every 16-row block: reads are contiguous across threads, its eight dims are one
+    // 16-byte store, and one pass with a running reference keeps a single round trip per partial.
     const int NBk = rows_per_group >> 4;
-    for (int idx = threadIdx.x; idx < NBk * 256; idx += 256) {
-        const int j = idx & 3, lane = (idx >> 2) & 63, nb = idx >> 8;
-        const int n = lane & 15, g = lane >> 4;
+    const int j = threadIdx.x & 3, lane = threadIdx.x >> 2;
+    const int n = lane & 15, g = lane >> 4;
+    float acc[4][8], mrun[4], den[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        mrun[nb] = -INFINITY;
+        den[nb] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[nb][e] = 0.f;
+    }
+    for (int k = jcut - 1; k < Wg; ++k) {
+        const int kbeg = slice_start(k), kend = slice_start(k + 1);
+        if (kbeg >= item_end) break;
+        if (kbeg == kend) continue;
+        const size_t slot = (size_t)slot_of(k, kbeg);
+        float m[4], l[4], o[4][8];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            if (nb < NBk) {
+                const size_t sl = slot * NBk + nb;
+                m[nb] = p.ws_ml[(sl * 16 + n) * 2];
+                l[nb] = p.ws_ml[(sl * 16 + n) * 2 + 1];
+                const float* src = p.ws_o + (sl * 8 * 64 + lane) * 4 + j;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[nb][e] = src[e * 256];
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            if (nb < NBk && m[nb] != -INFINITY) {   // a part in which the row saw no key adds nothing
+                const float mnew = fmaxf(mrun[nb], m[nb]);
+                const float aold = (mrun[nb] == -INFINITY) ? 0.f : fast_exp2(mrun[nb] - mnew);
+                const float anew = fast_exp2(m[nb] - mnew);
+                den[nb] = den[nb] * aold + l[nb] * anew;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[nb][e] = acc[nb][e] * aold + o[nb][e] * anew;
+                mrun[nb] = mnew;
+            }
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
         const int lrow = 16 * nb + n;
-        if (lrow >= nrows) continue;
-        float mstar = -INFINITY;
-        for (int k = jcut - 1; k < Wg; ++k) {
-            const int kbeg = slice_start(k), kend = slice_start(k + 1);
-            if (kbeg >= item_end) break;
-            if (kbeg == kend) continue;
-            mstar = fmaxf(mstar, p.ws_ml[(((size_t)slot_of(k, kbeg) * NBk + nb) * 16 + n) * 2]);
+        if (nb < NBk && lrow < nrows) {
+            const float inv = 1.f / den[nb];
+            const int row = rowbase + lrow;
+            const int i = row / p.G, gq = row - i * p.G;
+            bf16x8 ov;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ov[e] = (__bf16)(acc[nb][e] * inv);
+            uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + 32 * g + 8 * j;
+            *reinterpret_cast<bf16x8*>(op) = ov;
         }
-        float acc[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-        float den = 0.f;
-        for (int k = jcut - 1; k < Wg; ++k) {
-            const int kbeg = slice_start(k), kend = slice_start(k + 1);
-            if (kbeg >= item_end) break;
-            if (kbeg == kend) continue;
-            const size_t sl = (size_t)slot_of(k, kbeg) * NBk + nb;
-            const float m = p.ws_ml[(sl * 16 + n) * 2];
-            const float wgt = (m == -INFINITY) ? 0.f : fast_exp2(m - mstar);
-            den += wgt * p.ws_ml[(sl * 16 + n) * 2 + 1];
-            const float* src = p.ws_o + (sl * 8 * 64 + lane) * 4 + j;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] += src[e * 256] * wgt;
-        }
-        const float inv = 1.f / den;
-        const int row = rowbase + lrow;
-        const int i = row / p.G, gq = row - i * p.G;
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
-        uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + 32 * g + 8 * j;
-        *reinterpret_cast<bf16x8*>(op) = o;
     }
 }
 
