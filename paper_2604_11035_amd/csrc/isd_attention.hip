@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
 constexpr int kMaxWorkgroups = 1024;   // upper bound of the persistent grid (sizes the workspace)
 
@@ -41,8 +42,9 @@ struct AttnParams {
     const uint16_t* k;
     const uint16_t* v;
     uint16_t* out;
-    float* ws_o;    // [2*NW][NB][8][64][4] unnormalised partial outputs, accumulator registers as they are (slot 2v: first
-    float* ws_ml;   // [2*NW][NB][16][2]    sequence of wavefront v's slice, 2v+1: its last); (reference exponent, denominator)
+    u32x4* ws_o;    // [2*NW][NB][4][64] partial outputs of a slot (2v: first sequence of wavefront v's slice, 2v+1: its
+                    //                   last): eight fp16 per entry, normalised per row to a largest magnitude of 1
+    f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator, largest magnitude of O / denominator
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
@@ -193,6 +195,15 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     const int S = p.S, G = p.G, M = p.M;
     const float cs = p.scale_log2;
     u32x4* const qlds = qlds_all + (size_t)w * (NB * 4 * 64) + lane;
+    // a partial result waits here, in this wavefront's own LDS, until the wavefront has read all its K/V
+    u32x4* const stash_o = qlds_all + (size_t)(4 + w) * (NB * 4 * 64);
+    f32x4* const stash_ml = reinterpret_cast<f32x4*>(qlds_all + (size_t)8 * (NB * 4 * 64)) + w * (NB * 16);
+    auto flush_stash = [&](int slot) {
+        u32x4* dst = p.ws_o + (size_t)slot * (NB * 4 * 64) + lane;
+#pragma unroll
+        for (int q = 0; q < NB * 4; ++q) dst[q * 64] = stash_o[q * 64 + lane];
+        if (lane < NB * 16) p.ws_ml[(size_t)slot * (NB * 16) + lane] = stash_ml[lane];
+    };
 
     for (int vh = vh0; vh < VH; vh += vstep) {
         const int kvh = vh / p.RG;
@@ -229,8 +240,8 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                tk[0][s] = *reinterpret_cast<const bf16x8*>(k0 + klane + 32 * s);
-                tk[1][s] = *reinterpret_cast<const bf16x8*>(k1 + klane + 32 * s);
+                tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k0 + klane + 32 * s)));
+                tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k1 + klane + 32 * s)));
             }
         };
         auto load_v = [&](int pg0, int pg1) {
@@ -238,8 +249,8 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const uint16_t* v1 = vhp + (size_t)pg1 * p.page_stride;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tv[j] = *reinterpret_cast<const u32x4*>(v0 + j * p.token_stride + vlane);
-                tv[4 + j] = *reinterpret_cast<const u32x4*>(v1 + j * p.token_stride + vlane);
+                tv[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v0 + j * p.token_stride + vlane));
+                tv[4 + j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v1 + j * p.token_stride + vlane));
             }
         };
 
@@ -283,6 +294,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         load_q(b);
         store_q();
 
+        int stash_slot = -1;   // slot of the partial held in LDS, if any
         for (int i = 0; i < remaining;) {
             // ---- a sequence starts (or continues from an earlier slice); its Q is in this wavefront's
             //      LDS already, the accumulators restart ----
@@ -413,6 +425,11 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 // registers, and the reloads of what it spilled drain the memory counter between the
                 // stores).  An MFMA result needs up to 18 idle cycles before such a copy may read it.
                 asm volatile("s_nop 15\n\ts_nop 15");
+                // Stores that mix into the stream of K/V reads cost several times their share of the bytes
+                // (the memory goes back and forth between reading and writing), so a partial result is
+                // kept in LDS and written when the wavefront has no more K/V to read: the first sequence's
+                // until then, the last one's at once - after the first one's has left the LDS.
+                if (!complete && stash_slot >= 0) flush_stash(stash_slot);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     // denominators: add the four lanes (g = 0..3) that share a row
@@ -462,22 +479,37 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                             if (++gq == G) { gq = 0; ++ip; }
                         }
                     } else {
-                        // partial: the accumulators as they are, [nb][e][lane] quads (j = 0..3) = dims
-                        // 32g + 8j + e of local row 16nb + n; 1 KB per store instruction
-                        float* op = p.ws_o + ((wslot * NB + nb) * 8 * 64 + lane) * 4;
+                        // partial: each row scaled to a largest magnitude of 1 and kept as fp16, [nb][j][lane]
+                        // entries of dims 32g + 8j .. +7 of local row 16nb + n (the merge kernel's unit of work)
+                        float vals[8][4];
+                        float amax = 0.f;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) *reinterpret_cast<f32x4*>(op + e * 256) = oacc[e][nb];
-                        if (g == 0) {
-                            float* mp = p.ws_ml + ((wslot * NB + nb) * 16 + n) * 2;
-                            mp[0] = mref[nb];
-                            mp[1] = l;
+                        for (int e = 0; e < 8; ++e)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                vals[e][j] = acc_read(oacc[e][nb][j]);
+                                amax = fmaxf(amax, fabsf(vals[e][j]));
+                            }
+                        amax = fmaxf(amax, __shfl_xor(amax, 16));
+                        amax = fmaxf(amax, __shfl_xor(amax, 32));
+                        const float inv = amax > 0.f ? 1.f / amax : 0.f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            f16x8 hv;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) hv[e] = (_Float16)(vals[e][j] * inv);
+                            stash_o[(nb * 4 + j) * 64 + lane] = __builtin_bit_cast(u32x4, hv);
                         }
+                        // l > 0 whenever the row saw a key; the merge kernel skips rows whose reference is -inf
+                        if (g == 0) stash_ml[nb * 16 + n] = f32x4{mref[nb], l, l > 0.f ? amax / l : 0.f, 0.f};
                     }
                 }
+                if (!complete) stash_slot = (int)wslot;
             }
             store_q();
             b = pb; kt = pkt; nt = pnt;   // first tile of the next sequence (unused after the last one)
         }
+        if (stash_slot >= 0) flush_stash(stash_slot);
     }
 }
 
@@ -509,10 +541,11 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int kvh = vh / p.RG;
     const int rowbase = (vh - kvh * p.RG) * rows_per_group;
     const int nrows = min(rows_per_group, p.M - rowbase);
-    // partial layout: [slot][nb][e][lane = 16g+n][j] floats = dim 32g + 8j + e of local row
-    // 16nb + n; (reference exponent, denominator) at [slot][nb][n].  Thread (lane, j) gathers
-    // e = 0..7 of every 16-row block: reads are contiguous across threads, its eight dims are one
-    // 16-byte store, and one pass with a running reference keeps a single round trip per partial.
+    // partial layout: [slot][nb][j][lane = 16g+n] entries of eight fp16 = dims 32g + 8j .. +7 of local
+    // row 16nb + n, each row scaled to a largest magnitude of 1; (reference exponent, denominator,
+    // scale) at [slot][nb][n].  Thread (lane, j) handles one entry of every 16-row block: 16-byte
+    // loads contiguous across threads, one 16-byte store, and one pass with a running reference
+    // keeps a single round trip per partial.
     const int NBk = rows_per_group >> 4;
     const int j = threadIdx.x & 3, lane = threadIdx.x >> 2;
     const int n = lane & 15, g = lane >> 4;
@@ -529,27 +562,27 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
         if (kbeg >= item_end) break;
         if (kbeg == kend) continue;
         const size_t slot = (size_t)slot_of(k, kbeg);
-        float m[4], l[4], o[4][8];
+        f32x4 ml[4];
+        u32x4 o[4];
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
             if (nb < NBk) {
                 const size_t sl = slot * NBk + nb;
-                m[nb] = p.ws_ml[(sl * 16 + n) * 2];
-                l[nb] = p.ws_ml[(sl * 16 + n) * 2 + 1];
-                const float* src = p.ws_o + (sl * 8 * 64 + lane) * 4 + j;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[nb][e] = src[e * 256];
+                ml[nb] = p.ws_ml[sl * 16 + n];
+                o[nb] = p.ws_o[(sl * 4 + j) * 64 + lane];
             }
         }
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
-            if (nb < NBk && m[nb] != -INFINITY) {   // a part in which the row saw no key adds nothing
-                const float mnew = fmaxf(mrun[nb], m[nb]);
+            if (nb < NBk && ml[nb][0] != -INFINITY) {   // a part in which the row saw no key adds nothing
+                const float mnew = fmaxf(mrun[nb], ml[nb][0]);
                 const float aold = (mrun[nb] == -INFINITY) ? 0.f : fast_exp2(mrun[nb] - mnew);
-                const float anew = fast_exp2(m[nb] - mnew);
-                den[nb] = den[nb] * aold + l[nb] * anew;
+                const float anew = fast_exp2(ml[nb][0] - mnew);
+                den[nb] = den[nb] * aold + ml[nb][1] * anew;
+                const float wo = anew * ml[nb][1] * ml[nb][2];
+                const f16x8 hv = __builtin_bit_cast(f16x8, o[nb]);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[nb][e] = acc[nb][e] * aold + o[nb][e] * anew;
+                for (int e = 0; e < 8; ++e) acc[nb][e] = acc[nb][e] * aold + (float)hv[e] * wo;
                 mrun[nb] = mnew;
             }
         }
@@ -688,8 +721,8 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
     // two partial slots of 16*NB rows per wavefront of the largest grid
-    const size_t rows = (size_t)2 * kMaxWorkgroups * 4 * (16 * NB);
-    return rows * 128 * sizeof(float) + rows * 2 * sizeof(float);
+    const size_t slots = (size_t)2 * kMaxWorkgroups * 4;
+    return slots * NB * (4 * 64 * sizeof(u32x4) + 16 * sizeof(f32x4));
 }
 
 extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
@@ -760,17 +793,21 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     int NB;
     row_tiling(p.M, &NB, &p.RG);
     p.Mpad = 16 * NB;
-    const size_t rows = (size_t)2 * kMaxWorkgroups * 4 * p.Mpad;
-    p.ws_o = static_cast<float*>(workspace);
-    p.ws_ml = p.ws_o + rows * 128;
+    const size_t slots = (size_t)2 * kMaxWorkgroups * 4;
+    p.ws_o = static_cast<u32x4*>(workspace);
+    p.ws_ml = reinterpret_cast<f32x4*>(p.ws_o + slots * NB * 4 * 64);
     p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
     p.scale_log2 = scale * kLog2e;
 
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
-    const size_t shmem = (size_t)4 * NB * 4 * 64 * 16;   // Q operands of the four wavefronts' current sequences
-    if (NB == 4)   // 64 KB of Q operands plus the static plan exceed the default 64 KB limit
+    // per wavefront: Q operands of its current sequence, one parked partial result, that partial's row scalars
+    const size_t shmem = (size_t)4 * NB * (4 * 64 * 16 * 2 + 16 * 16);
+    if (NB == 4)   // beyond the default 64 KB limit
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    else if (NB == 2)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<2>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (NB == 1) hipLaunchKernelGGL(isd_attention_bf16_kernel<1>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
     else if (NB == 2) hipLaunchKernelGGL(isd_attention_bf16_kernel<2>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
