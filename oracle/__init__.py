@@ -51,6 +51,10 @@ def lib() -> C.CDLL:
         L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.isd_oracle_row_stats.restype = C.c_int
         L.isd_oracle_num_threads.restype = C.c_int
+        L.isd_oracle_kv_append.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 7 + [C.c_int64] * 3 + [C.c_int32]
+        L.isd_oracle_kv_append.restype = C.c_int
+        L.isd_oracle_commit.argtypes = [C.c_void_p] * 8 + [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 6
+        L.isd_oracle_commit.restype = C.c_int
         _lib = L
     return _lib
 
@@ -165,3 +169,48 @@ def row_stats(row):
     if rc != 0:
         raise ValueError("isd_oracle_row_stats failed")
     return m.value, z.value, a.value
+
+
+def kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S, *, Hkv, D, P, strides=None):
+    """Scatters the stride's K/V rows [B,S,Hkv,D] into the paged caches IN PLACE (numpy arrays
+    of uint16 bit patterns or float32, C-contiguous storage).  Raises on a broken precondition."""
+    dtype = 1 if k_new.dtype == np.uint16 else 0
+    want = np.uint16 if dtype == 1 else np.float32
+    for a in (k_new, v_new, k_cache, v_cache):
+        assert a.dtype == want and a.flags["C_CONTIGUOUS"]
+    block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    B = ctx_lens.shape[0]
+    assert k_new.size == B * S * Hkv * D and v_new.size == k_new.size
+    if strides is None:
+        num_pages = k_cache.size // (Hkv * P * D)
+        strides = (Hkv * P * D, P * D, D)
+    else:
+        num_pages = (k_cache.size - 1) // strides[0] + 1
+    rc = lib().isd_oracle_kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                    _ptr(ctx_lens), S, B, Hkv, D, P, num_pages, block_table.shape[1],
+                                    strides[0], strides[1], strides[2], dtype)
+    if rc != 0:
+        raise ValueError("isd_oracle_kv_append failed: %d" % rc)
+
+
+def commit(state, accept_len, new_tokens, *, n_draft_steady, mask_token, P):
+    """Trim-and-commit plus preparation of the next stride, IN PLACE on `state`, a dict of int32
+    numpy arrays: n_draft [B], ctx_lens [B], stride_tokens [B,S], draft_tokens [B,S-1],
+    out_tokens [B,cap], out_lens [B], block_table [B,max_pages], pages_used [B], free_list [F],
+    free_top [1].  Returns the status word (0 done, 1 free list too short, 2 table row too short)."""
+    for k, v in state.items():
+        assert v.dtype == np.int32 and v.flags["C_CONTIGUOUS"], k
+    accept_len = np.ascontiguousarray(accept_len, dtype=np.int32)
+    new_tokens = np.ascontiguousarray(new_tokens, dtype=np.int32)
+    B, S = new_tokens.shape
+    status = np.full(1, -1, dtype=np.int32)
+    rc = lib().isd_oracle_commit(_ptr(accept_len), _ptr(new_tokens), _ptr(state["n_draft"]), _ptr(state["ctx_lens"]),
+                                 _ptr(state["stride_tokens"]), _ptr(state["draft_tokens"]) if S > 1 else None,
+                                 _ptr(state["out_tokens"]), _ptr(state["out_lens"]), state["out_tokens"].shape[1],
+                                 _ptr(state["block_table"]), _ptr(state["pages_used"]), _ptr(state["free_list"]),
+                                 _ptr(state["free_top"]), _ptr(status), int(n_draft_steady), int(mask_token),
+                                 B, S, P, state["block_table"].shape[1])
+    if rc != 0:
+        raise ValueError("isd_oracle_commit failed: %d" % rc)
+    return int(status[0])

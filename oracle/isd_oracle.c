@@ -17,6 +17,10 @@
  *     when every draft passes, arg-max proposals from the MASK rows.
  *   - the counter-based generator Philox4x32-10 (Salmon et al., SC'11) that
  *     supplies the uniforms of the accept test and of the Gumbel-max sampler.
+ *   - the two steps that close the loop between consecutive ISD steps (Sec. 3.3
+ *     (2): forward -> verify -> trim -> prepare -> forward): the batched scatter
+ *     of the stride's K/V rows into the pages (kv_append), and trim-and-commit
+ *     plus preparation of the next stride (commit) after Alg. 1's last line.
  *
  * Pins (tests that check this file against something other than itself) are in
  * tests/test_oracle_*.py; every function here has at least one.
@@ -320,6 +324,118 @@ int isd_oracle_accept(const float* logits, const int32_t* draft_tokens, uint64_t
         free(m); free(Z); free(a);
     }
     return status;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Between two steps: KV append, trim-and-commit, next stride                */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Batched scatter of the stride's K/V rows into the paged cache (Sec. 3.3 (1):
+ * each ISD step appends its 2N-1 tokens in extend mode; (2): "KV slots are
+ * allocated via a single batched scatter").  Row i of sequence b belongs to
+ * absolute position t = ctx_lens[b]-S+i (ctx_lens counts the S rows) and goes to
+ * page block_table[b][t/P], slot t%P, for every KV head.
+ * k_new / v_new [B,S,Hkv,D] contiguous; cache addressing as in attention.
+ * dtype 0 = 4-byte elements, 1 = 2-byte elements (bit patterns are copied).
+ * A position outside the table or a page id outside the pool is an error here
+ * (the oracle refuses; nothing more is written).
+ */
+int isd_oracle_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                         const int32_t* block_table, const int32_t* ctx_lens, int32_t S, int32_t B,
+                         int32_t Hkv, int32_t D, int32_t P, int32_t num_pages, int32_t max_pages_per_seq,
+                         int64_t page_stride, int64_t head_stride, int64_t token_stride, int32_t dtype)
+{
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_table || !ctx_lens) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || Hkv < 1 || D < 1 || P < 1 || (dtype != 0 && dtype != 1)) return ORACLE_ERR_ARG;
+    const size_t esz = dtype == 0 ? 4 : 2;
+    for (int b = 0; b < B; ++b)
+        for (int i = 0; i < S; ++i) {
+            const int64_t t = (int64_t)ctx_lens[b] - S + i;
+            if (t < 0 || t / P >= max_pages_per_seq) return ORACLE_ERR_ARG;
+            const int32_t page = block_table[(int64_t)b * max_pages_per_seq + t / P];
+            if (page < 0 || page >= num_pages) return ORACLE_ERR_TABLE;
+            const int slot = (int)(t % P);
+            for (int h = 0; h < Hkv; ++h) {
+                const int64_t src = (((int64_t)b * S + i) * Hkv + h) * D;
+                const int64_t dst = page * page_stride + h * head_stride + slot * token_stride;
+                memcpy((char*)k_cache + dst * esz, (const char*)k_new + src * esz, D * esz);
+                memcpy((char*)v_cache + dst * esz, (const char*)v_new + src * esz, D * esz);
+            }
+        }
+    return ORACLE_OK;
+}
+
+/*
+ * Trim-and-commit after verification, and the next stride (Alg. 1, last line:
+ * "append x_{L+1 : L+n_accepted} to prefix; commit KV cache"; Sec. 3.2: after a
+ * rejection "all subsequent tokens are discarded; the next step becomes a pure
+ * stride with no tokens to introspect"; Sec. 3.3 (2): the trim-and-commit cycle
+ * "frees rejected and MASK positions after each verification").
+ *
+ * For sequence b with D = n_draft[b] drafts verified this step and r =
+ * accept_len[b] of them accepted (0 <= r <= D <= S-1):
+ *   - the step finalises r+1 tokens, new_tokens[b][0..r] (the accepted drafts and
+ *     the freshly sampled token), appended to out_tokens[b] (at most out_cap kept);
+ *   - of the stride's S KV slots the first r+1 stay (the step's first input token
+ *     and the accepted drafts); the rest - rejected drafts and MASK positions - are
+ *     given back: the context shrinks to ctx-S+r+1;
+ *   - the next stride starts with the fresh token.  If nothing was rejected (r = D)
+ *     it carries nd = min(n_draft_steady, S-1-D) drafts, the arg-max proposals of
+ *     the MASK rows new_tokens[b][D+1 .. D+nd]; after a rejection it carries none.
+ *     The remaining positions hold mask_token.  draft_tokens_next[b][0..nd) repeats
+ *     the drafts in the layout the acceptance pass reads ([B,S-1]), -1 beyond;
+ *   - the next stride's S positions are appended at once: ctx_lens[b] becomes
+ *     ctx-S+r+1+S = ctx+r+1, and pages for positions that have none yet are popped
+ *     from the top of free_list (entries free_list[0 .. *free_top)), sequence by
+ *     sequence in index order, each sequence's pages in ascending position order.
+ * If the free list cannot cover the whole batch (*status = 1) or a sequence would
+ * outgrow its block-table row (*status = 2) nothing at all is changed.
+ * Returns ORACLE_ERR_ARG for malformed arguments (including r or D out of range).
+ */
+int isd_oracle_commit(const int32_t* accept_len, const int32_t* new_tokens, int32_t* n_draft,
+                      int32_t* ctx_lens, int32_t* stride_tokens, int32_t* draft_tokens_next,
+                      int32_t* out_tokens, int32_t* out_lens, int32_t out_cap, int32_t* block_table,
+                      int32_t* pages_used, const int32_t* free_list, int32_t* free_top, int32_t* status,
+                      int32_t n_draft_steady, int32_t mask_token, int32_t B, int32_t S, int32_t P,
+                      int32_t max_pages_per_seq)
+{
+    if (!accept_len || !new_tokens || !n_draft || !ctx_lens || !stride_tokens || !out_tokens ||
+        !out_lens || !block_table || !pages_used || !free_list || !free_top || !status)
+        return ORACLE_ERR_ARG;
+    if (S > 1 && !draft_tokens_next) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || P < 1 || max_pages_per_seq < 1 || out_cap < 0 || n_draft_steady < 0) return ORACLE_ERR_ARG;
+    int64_t need = 0;
+    for (int b = 0; b < B; ++b) {
+        const int r = accept_len[b], D = n_draft[b];
+        if (D < 0 || D > S - 1 || r < 0 || r > D) return ORACLE_ERR_ARG;
+        const int64_t pages = ((int64_t)ctx_lens[b] + r + 1 + P - 1) / P;
+        if (pages > max_pages_per_seq) { *status = 2; return ORACLE_OK; }
+        if (pages > pages_used[b]) need += pages - pages_used[b];
+    }
+    if (need > *free_top) { *status = 1; return ORACLE_OK; }
+    int32_t top = *free_top;
+    for (int b = 0; b < B; ++b) {
+        const int r = accept_len[b], D = n_draft[b];
+        const int32_t* nt = new_tokens + (int64_t)b * S;
+        for (int j = 0; j <= r; ++j)
+            if (out_lens[b] < out_cap) out_tokens[(int64_t)b * out_cap + out_lens[b]++] = nt[j];
+        int nd = 0;
+        if (r == D) nd = n_draft_steady < S - 1 - D ? n_draft_steady : S - 1 - D;
+        int32_t* st = stride_tokens + (int64_t)b * S;
+        st[0] = nt[r];
+        for (int k = 0; k < nd; ++k) st[1 + k] = nt[D + 1 + k];
+        for (int k = 1 + nd; k < S; ++k) st[k] = mask_token;
+        for (int k = 0; k < S - 1; ++k) draft_tokens_next[(int64_t)b * (S - 1) + k] = k < nd ? st[1 + k] : -1;
+        const int32_t ctx_next = ctx_lens[b] + r + 1;
+        const int32_t pages = (ctx_next + P - 1) / P;
+        while (pages_used[b] < pages) block_table[(int64_t)b * max_pages_per_seq + pages_used[b]++] = free_list[--top];
+        n_draft[b] = nd;
+        ctx_lens[b] = ctx_next;
+    }
+    *free_top = top;
+    *status = 0;
+    return ORACLE_OK;
 }
 
 /* Row statistics alone (m, Z, arg-max) for spot checks of very large inputs. */
