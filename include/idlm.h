@@ -163,6 +163,59 @@ int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_
 /* Bytes of workspace idlm_isd_accept needs (host-only). Returns 0 for rejected shapes. */
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
 
+/*
+ * idlm_isd_kv_append - batched scatter of the stride's K/V rows into the paged cache, before the
+ * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): "KV slots
+ * are allocated via a single batched scatter").
+ *
+ * Row i of sequence b belongs to absolute position t = ctx_lens[b]-S+i (ctx_lens counts the S
+ * rows, as in idlm_isd_attention) and is copied, for every KV head, to page block_table[b][t/P],
+ * slot t%P of both pools.  Slots of a previous stride that were given back are simply overwritten.
+ * A row whose position is negative or beyond the table row, or whose page id is outside
+ * [0,num_pages), is skipped (nothing is written for it).
+ *
+ * k_new, v_new [B,S,Hkv,D] contiguous, element type `dtype`, 16-byte aligned; D*sizeof(element) a
+ *              multiple of 16.
+ * k_cache,     page pools addressed as in idlm_isd_attention (strides in elements).
+ * v_cache
+ * Supported: 0 <= B <= 65535, 1 <= S <= 64, any P >= 1.  Bit patterns are copied unchanged.
+ */
+int idlm_isd_kv_append(const void* k_new, const void* v_new, void* k_cache, void* v_cache,
+                       const int32_t* block_table, const int32_t* ctx_lens, int32_t S, int32_t B,
+                       int32_t Hkv, int32_t D, int32_t P, int32_t num_pages, int32_t max_pages_per_seq,
+                       int64_t page_stride, int64_t head_stride, int64_t token_stride, int32_t dtype,
+                       void* stream);
+
+/*
+ * idlm_isd_commit - trim-and-commit after idlm_isd_accept, and the next stride (Alg. 1, last
+ * line: the accepted tokens join the prefix and the KV cache is committed; Sec. 3.2 "Adaptive
+ * stride via p/q acceptance": after a rejection the rest is discarded and the next step is a pure
+ * stride; Sec. 3.3 (2): the trim-and-commit cycle frees rejected and MASK positions).
+ *
+ * For sequence b with D = n_draft[b] and r = accept_len[b] (0 <= r <= D <= S-1):
+ *   - new_tokens[b][0..r] (accepted drafts, then the fresh token) are appended to out_tokens[b]
+ *     (row stride out_cap; tokens beyond out_cap are dropped) and out_lens[b] grows accordingly;
+ *   - the stride's first r+1 KV slots stay, the others are given back, and the next stride's S
+ *     positions are appended at once: ctx_lens[b] += r+1;
+ *   - stride_tokens[b] = fresh token, then nd drafts, then mask_token; nd = min(n_draft_steady,
+ *     S-1-D) arg-max proposals new_tokens[b][D+1 .. D+nd] if nothing was rejected (r = D), else 0;
+ *     draft_tokens_next[b] ([B,S-1], the layout idlm_isd_accept reads) repeats the drafts, -1
+ *     beyond; n_draft[b] = nd;
+ *   - positions that have no page yet get one: block_table[b][pages_used[b]++] = free_list[--top],
+ *     sequences in index order, starting from top = *free_top; *free_top is updated.
+ * *status: 0 done; 1 the free list cannot cover the batch; 2 a sequence would outgrow its table
+ * row; 3 an accept_len / n_draft pair is out of range.  For a non-zero status NOTHING is changed.
+ * All arrays int32 on the device, 4-byte aligned; n_draft, ctx_lens, out_lens, block_table,
+ * pages_used, free_top are updated in place.  draft_tokens_next may be NULL iff S = 1.
+ * Supported: 0 <= B <= 65535, 1 <= S <= 64.  One small launch; asynchronous on `stream`.
+ */
+int idlm_isd_commit(const int32_t* accept_len, const int32_t* new_tokens, int32_t* n_draft,
+                    int32_t* ctx_lens, int32_t* stride_tokens, int32_t* draft_tokens_next,
+                    int32_t* out_tokens, int32_t* out_lens, int32_t out_cap, int32_t* block_table,
+                    int32_t* pages_used, const int32_t* free_list, int32_t* free_top, int32_t* status,
+                    int32_t n_draft_steady, int32_t mask_token, int32_t B, int32_t S, int32_t P,
+                    int32_t max_pages_per_seq, void* stream);
+
 /* Static, NUL-terminated description of a return code (host pointer, never NULL). */
 const char* idlm_strerror(int code);
 

@@ -49,6 +49,10 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_ev.restype = C.c_int
         L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_workspace.restype = C.c_size_t
+        L.idlm_isd_kv_append.argtypes = [vp] * 6 + [i32] * 7 + [i64] * 3 + [i32, vp]
+        L.idlm_isd_kv_append.restype = C.c_int
+        L.idlm_isd_commit.argtypes = [vp] * 8 + [i32] + [vp] * 5 + [i32] * 6 + [vp]
+        L.idlm_isd_commit.restype = C.c_int
         L.idlm_strerror.argtypes = [C.c_int]
         L.idlm_strerror.restype = C.c_char_p
         L.idlm_version.restype = C.c_int
@@ -178,3 +182,39 @@ def idlm_stream_read(src, sink, stream=None):
     rc = lib().idlm_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_stream_read")
+
+
+def idlm_isd_kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S, *, stream=None):
+    """Scatters the stride's K/V rows [B,S,Hkv,D] into the paged pools (see idlm.h)."""
+    B, S_, Hkv, D = k_new.shape
+    assert S_ == S and v_new.shape == k_new.shape and k_new.is_contiguous() and v_new.is_contiguous()
+    num_pages, Hkv_c, P, Dk = k_cache.shape
+    assert Hkv_c == Hkv and Dk == D and v_cache.shape == k_cache.shape and v_cache.stride() == k_cache.stride()
+    assert k_cache.stride(3) == 1 and k_cache.dtype == k_new.dtype == v_new.dtype == v_cache.dtype
+    assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
+    assert block_table.is_contiguous() and ctx_lens.is_contiguous() and block_table.shape[0] == B
+    rc = lib().idlm_isd_kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
+                                  _ptr(ctx_lens), S, B, Hkv, D, P, num_pages, block_table.shape[1],
+                                  k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), _dtype_code(k_new),
+                                  _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_kv_append")
+
+
+def idlm_isd_commit(accept_len, new_tokens, state, *, n_draft_steady, mask_token, P, stream=None):
+    """Trim-and-commit plus the next stride, in place on `state`: a dict of int32 device tensors
+    n_draft [B], ctx_lens [B], stride_tokens [B,S], draft_tokens [B,S-1], out_tokens [B,cap],
+    out_lens [B], block_table [B,max_pages], pages_used [B], free_list [F], free_top [1],
+    status [1] (see idlm.h).  Asynchronous: read state["status"] after synchronising."""
+    B, S = new_tokens.shape
+    for k, v in state.items():
+        assert v.dtype == torch.int32 and v.is_contiguous(), k
+    assert accept_len.dtype == torch.int32 and new_tokens.dtype == torch.int32 and new_tokens.is_contiguous()
+    rc = lib().idlm_isd_commit(_ptr(accept_len), _ptr(new_tokens), _ptr(state["n_draft"]), _ptr(state["ctx_lens"]),
+                               _ptr(state["stride_tokens"]), _ptr(state["draft_tokens"]) if S > 1 else None,
+                               _ptr(state["out_tokens"]), _ptr(state["out_lens"]), state["out_tokens"].shape[1],
+                               _ptr(state["block_table"]), _ptr(state["pages_used"]), _ptr(state["free_list"]),
+                               _ptr(state["free_top"]), _ptr(state["status"]), int(n_draft_steady), int(mask_token),
+                               B, S, P, state["block_table"].shape[1], _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_commit")
