@@ -234,6 +234,39 @@ def main():
               "bytes": probe.numel()}
     del probe, probe_dst
 
+    # the two small kernels between steps (scatter of the stride's K/V rows; trim-and-commit and next
+    # stride), timed on the same workload outside the timed region above
+    k_new = torch.randn(B, S, cfg.Hkv, cfg.D, device=dev).to(att.q.dtype)
+    v_new = torch.randn(B, S, cfg.Hkv, cfg.D, device=dev).to(att.q.dtype)
+    t_append = timed(lambda: idlm.idlm_isd_kv_append(k_new, v_new, att.k_cache, att.v_cache, att.block_table,
+                                                     att.ctx_lens, S), n=20)
+    pages_used = (att.ctx_lens + cfg.P - 1) // cfg.P
+    n_steady = max(0, (S - 1) // 2)
+
+    def commit_state():
+        return dict(n_draft=acc.n_draft.clone(), ctx_lens=(att.ctx_lens - 64).clamp(min=S).contiguous(),
+                    stride_tokens=torch.empty(B, S, dtype=torch.int32, device=dev),
+                    draft_tokens=torch.empty(B, max(S - 1, 1), dtype=torch.int32, device=dev)[:, :S - 1].contiguous(),
+                    out_tokens=torch.empty(B, 64, dtype=torch.int32, device=dev),
+                    out_lens=torch.zeros(B, dtype=torch.int32, device=dev), block_table=att.block_table.clone(),
+                    pages_used=pages_used.to(torch.int32).contiguous(),
+                    free_list=torch.arange(4 * B, dtype=torch.int32, device=dev),
+                    free_top=torch.full((1,), 4 * B, dtype=torch.int32, device=dev),
+                    status=torch.full((1,), -1, dtype=torch.int32, device=dev))
+
+    states = [commit_state() for _ in range(21)]
+    it = iter(states)
+    t_commit = timed(lambda: idlm.idlm_isd_commit(accept_len, new_tokens, next(it), n_draft_steady=n_steady,
+                                                  mask_token=cfg.V - 1, P=cfg.P), n=20)
+    commit_ok = all(int(st_["status"].item()) == 0 for st_ in states)
+    append_bytes = 2 * 2 * B * S * cfg.Hkv * cfg.D * att.q.element_size()
+    loop_kernels = {
+        "isd_kv_append_kernel": {"ms": t_append, "bytes_read_plus_written": append_bytes,
+                                 "GBps": append_bytes / t_append / 1e6},
+        "isd_commit_kernel": {"ms": t_commit, "status_ok": commit_ok},
+    }
+    del states
+
     cpu = None
     if args.cpu_sample > 0 and cfg.dtype == "bf16":
         cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
@@ -260,6 +293,7 @@ def main():
         "cpu_baseline": cpu,
         "kernels": kernels,
         "stream_ceiling": stream_probe,
+        "between_steps": loop_kernels,
         "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
                           "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }
