@@ -114,3 +114,49 @@ def test_stream_helpers_validate():
     assert L.idlm_stream_copy(ODD, FAKE, 16, None) == -4
     assert L.idlm_stream_copy(FAKE, FAKE, 0, None) == 0
     assert L.idlm_stream_read(FAKE, 32, None, None) == -1
+
+
+def _append(**kw):
+    a = dict(kn=FAKE, vn=FAKE, kc=FAKE, vc=FAKE, table=FAKE, ctx=FAKE, S=4, B=2, Hkv=2, D=128, P=16, num_pages=10,
+             max_pages=4, ps=2 * 16 * 128, hs=16 * 128, ts=128, dtype=1, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_kv_append(a["kn"], a["vn"], a["kc"], a["vc"], a["table"], a["ctx"], a["S"], a["B"],
+                                         a["Hkv"], a["D"], a["P"], a["num_pages"], a["max_pages"], a["ps"], a["hs"],
+                                         a["ts"], a["dtype"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(kn=None), -1), (dict(vc=None), -1), (dict(ctx=None), -1),
+    (dict(S=0), -2), (dict(S=65), -2), (dict(B=70000), -2), (dict(num_pages=0), -2), (dict(ts=64), -2),
+    (dict(dtype=5), -3),
+    (dict(kn=ODD), -4), (dict(kc=ODD), -4), (dict(D=4), -4), (dict(ts=132), -4),
+])
+def test_kv_append_rejects_bad_arguments(kw, code):
+    assert _append(**kw) == code
+
+
+def test_kv_append_empty_batch_is_ok_without_device():
+    assert _append(B=0) == 0
+
+
+def _commit(**kw):
+    a = dict(alen=FAKE, toks=FAKE, nd=FAKE, ctx=FAKE, stride=FAKE, drafts=FAKE, out=FAKE, olen=FAKE, cap=32,
+             table=FAKE, used=FAKE, free=FAKE, top=FAKE, status=FAKE, steady=3, mask=9, B=2, S=7, P=16, max_pages=8,
+             stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_commit(a["alen"], a["toks"], a["nd"], a["ctx"], a["stride"], a["drafts"], a["out"],
+                                      a["olen"], a["cap"], a["table"], a["used"], a["free"], a["top"], a["status"],
+                                      a["steady"], a["mask"], a["B"], a["S"], a["P"], a["max_pages"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(alen=None), -1), (dict(status=None), -1), (dict(free=None), -1), (dict(drafts=None), -1),
+    (dict(S=0), -2), (dict(S=65), -2), (dict(B=-1), -2), (dict(cap=-1), -2), (dict(steady=-1), -2), (dict(max_pages=0), -2),
+    (dict(ctx=C.c_void_p(0x1002)), -4),
+])
+def test_commit_rejects_bad_arguments(kw, code):
+    assert _commit(**kw) == code
+
+
+def test_commit_empty_batch_is_ok_without_device():
+    assert _commit(B=0) == 0
