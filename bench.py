@@ -123,6 +123,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="serve256")
+    ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
     ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
@@ -137,7 +138,7 @@ def main():
     import paper_2604_11035_amd as idlm
     from isd_inputs import get_config, make_accept_inputs, make_attention_inputs
 
-    cfg = get_config(args.workload)
+    cfg = get_config(args.workload, **({"S": args.stride} if args.stride else {}))
     dev = "cuda:0"
     torch.cuda.set_device(0)
     att = make_attention_inputs(cfg, device=dev)
