@@ -238,3 +238,83 @@ def test_several_steps_of_the_whole_loop(N, greedy):
         finalised += int((r["accept_len"] + 1).sum())
     assert (st["out_lens"] >= steps).all() and st["out_lens"].sum() == finalised
     assert finalised > B * steps                      # some drafts were accepted
+
+
+def test_the_loop_replays_from_a_captured_graph():
+    """The four calls of a step allocate nothing and never synchronise, so a caller can capture
+    them in a HIP graph and replay it step after step with the inputs refreshed in place (the
+    deployment the paper describes in Sec. 3.3 (1)).  Every replay is checked against the oracle,
+    with eager work and synchronisations in between."""
+    N, steps = 3, 5
+    rng = np.random.default_rng(123)
+    B, S, Hq, Hkv, D, P, V = 12, 2 * N - 1, 8, 2, 128, 16, 2048
+    max_pages = 12
+    ctx0 = (rng.integers(20, 90, size=B) + S).astype(np.int32)
+    pages_used = ((ctx0 + P - 1) // P).astype(np.int32)
+    num_pages = int(pages_used.sum()) + B * 3 + 4
+    perm = rng.permutation(num_pages).astype(np.int32)
+    table = np.full((B, max_pages), -1, np.int32)
+    k = 0
+    for b in range(B):
+        table[b, :pages_used[b]] = perm[k:k + pages_used[b]]; k += pages_used[b]
+    free = perm[k:].copy()
+    st = dict(n_draft=np.zeros(B, np.int32), ctx_lens=ctx0.copy(), stride_tokens=np.full((B, S), MASK, np.int32),
+              draft_tokens=np.full((B, S - 1), -1, np.int32), out_tokens=np.full((B, 40), -9, np.int32),
+              out_lens=np.zeros(B, np.int32), block_table=table, pages_used=pages_used, free_list=free,
+              free_top=np.array([len(free)], np.int32))
+    g = to_gpu(st)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    kc = torch.randn(num_pages, Hkv, P, D, device=DEV).to(torch.bfloat16)
+    vc = torch.randn(num_pages, Hkv, P, D, device=DEV).to(torch.bfloat16)
+    o_kc, o_vc = bits(kc).copy(), bits(vc).copy()
+    # static buffers the graph reads and writes
+    kn = torch.zeros(B, S, Hkv, D, dtype=torch.bfloat16, device=DEV); vn = torch.zeros_like(kn)
+    q = torch.zeros(B, S, Hq, D, dtype=torch.bfloat16, device=DEV); out = torch.zeros_like(q)
+    logits = torch.zeros(B, S, V, dtype=torch.float32, device=DEV)
+    drafts_in = torch.zeros(B, S - 1, dtype=torch.int32, device=DEV)
+    accept_len = torch.zeros(B, dtype=torch.int32, device=DEV); new_tokens = torch.zeros(B, S, dtype=torch.int32, device=DEV)
+    greedy = torch.ones(B, dtype=torch.uint8, device=DEV)
+    ws_a = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages, 1)), dtype=torch.uint8, device=DEV)
+    ws_c = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=DEV)
+
+    def step_calls(stream):
+        idlm.idlm_isd_kv_append(kn, vn, kc, vc, g["block_table"], g["ctx_lens"], S, stream=stream)
+        idlm.idlm_isd_attention(q, kc, vc, g["block_table"], g["ctx_lens"], S, out, workspace=ws_a, stream=stream)
+        idlm.idlm_isd_accept(logits, drafts_in, 777, accept_len, new_tokens, n_draft=g["n_draft"], greedy=greedy,
+                             rng_offset=0, workspace=ws_c, stream=stream)
+        idlm.idlm_isd_commit(accept_len, new_tokens, g, n_draft_steady=N - 1, mask_token=MASK, P=P, stream=stream)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    snapshot = {k_: v.clone() for k_, v in g.items()}
+    kc_snap, vc_snap = kc.clone(), vc.clone()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        step_calls(side)
+    torch.cuda.synchronize()
+    for k_, v in snapshot.items():      # capture does not run anything, but start from a known state anyway
+        g[k_].copy_(v)
+    kc.copy_(kc_snap); vc.copy_(vc_snap)
+    for step in range(steps):
+        h_kn, h_vn, h_q = (rng.standard_normal(sh).astype(np.float32) for sh in ((B, S, Hkv, D), (B, S, Hkv, D), (B, S, Hq, D)))
+        kn.copy_(torch.from_numpy(h_kn)); vn.copy_(torch.from_numpy(h_vn)); q.copy_(torch.from_numpy(h_q))
+        h_drafts = np.where(st["draft_tokens"] >= 0, st["draft_tokens"], 0).astype(np.int32)
+        h_logits = (rng.standard_normal((B, S, V)) * 2).astype(np.float32)
+        bi, ji = np.meshgrid(np.arange(B), np.arange(S - 1), indexing="ij")
+        h_logits[bi, ji, h_drafts] += rng.choice([0.0, 14.0], size=(B, S - 1), p=[0.3, 0.7]).astype(np.float32)
+        logits.copy_(torch.from_numpy(h_logits)); drafts_in.copy_(torch.from_numpy(h_drafts))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        oracle.kv_append(bits(kn), bits(vn), o_kc, o_vc, st["block_table"], st["ctx_lens"], S, Hkv=Hkv, D=D, P=P)
+        assert np.array_equal(bits(kc), o_kc) and np.array_equal(bits(vc), o_vc), step
+        ref = oracle.attention(bits(q), o_kc, o_vc, st["block_table"], st["ctx_lens"], S, Hq=Hq, Hkv=Hkv, D=D, P=P)
+        err, _ = attention_errors(out.float().cpu().numpy().astype(np.float64), ref)
+        assert err <= ATTN_REL_TOL, step
+        r = oracle.accept(h_logits, h_drafts, 777, n_draft=st["n_draft"], greedy=np.ones(B, np.uint8), rng_offset=0)
+        assert np.array_equal(accept_len.cpu().numpy(), r["accept_len"]), step
+        assert np.array_equal(new_tokens.cpu().numpy(), r["new_tokens"]), step
+        assert oracle.commit(st, r["accept_len"], r["new_tokens"], n_draft_steady=N - 1, mask_token=MASK, P=P) == 0
+        assert int(g["status"].item()) == 0
+        assert_same(g, st)
+        _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()      # unrelated eager work between replays
