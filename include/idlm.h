@@ -19,6 +19,9 @@
  *     ceil(ctx_lens[b]/P) <= max_pages_per_seq; block_table[b][p] in
  *     [0,num_pages) for p < ceil(ctx_lens[b]/P) (entries beyond that are never
  *     read); draft token ids in [0,V); n_draft[b] in [0,S-1]; logits hold no NaN.
+ *     A broken precondition gives meaningless results, never an access outside
+ *     the caller's buffers as far as the sizes passed on the host allow to tell
+ *     (context lengths are cut at the table row, page ids are forced into the pool).
  *   - No global mutable state; entry points may be called from several host
  *     threads.  No C++ exception crosses this boundary.
  */

@@ -9,8 +9,10 @@
 // ("stream-K"), which it finds with a block-wide prefix sum over ctx_lens: no host round trip,
 // no empty workgroups, equal bytes per wavefront whatever the length mix, and no barrier after
 // the prefix sum.  A sequence that lies wholly inside a slice is written out directly; one that
-// a slice boundary cuts leaves an fp32 partial (at most two per wavefront) that a small second
-// kernel joins.
+// a slice boundary cuts leaves a partial result (at most two per wavefront: row-scaled fp16 plus
+// per-row reference exponent, denominator and scale) that a small second kernel joins.  Partials
+// wait in the wavefront's LDS until it has read all its K/V: stores that mix into the stream of
+// reads cost several times their share of the bytes on this memory system.
 //
 // For a tile the S*G query rows that share the KV head form the N side of every MFMA and
 // everything is computed transposed, so that no cross-lane data movement is needed between
@@ -44,8 +46,9 @@ struct AttnParams {
     uint16_t* out;
     u32x4* ws_o;    // [2*NW][NB][4][64] partial outputs of a slot (2v: first sequence of wavefront v's slice, 2v+1: its
                     //                   last): eight fp16 per entry, normalised per row to a largest magnitude of 1
-    f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator, largest magnitude of O / denominator
+    f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator l, largest magnitude of O / l, unused
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
+    int num_pages;
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
 };
@@ -221,6 +224,10 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const int npages = (min(ctx_lens[b], p.max_pages * 16) + 15) >> 4;
             pg0 = tab[2 * kt];
             pg1 = (2 * kt + 1 < npages) ? tab[2 * kt + 1] : pg0;
+            // a page id outside the pool breaks the caller's side of the contract; the read stays inside the
+            // pool anyway (two scalar instructions)
+            pg0 = min(max(pg0, 0), p.num_pages - 1);
+            pg1 = min(max(pg1, 0), p.num_pages - 1);
         };
         // next tile of the slice: the next tile of the sequence, or tile 0 of the next non-empty one
         auto advance = [&](int& b, int& kt, int& nt) {
@@ -611,7 +618,7 @@ struct AttnParamsF32 {
     const int32_t* table;
     const int32_t* ctx;
     float* out;
-    int S, Hq, Hkv, G, P, max_pages;
+    int S, Hq, Hkv, G, P, max_pages, num_pages;
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
 };
@@ -631,7 +638,7 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
     for (int d = 0; d < D; ++d) o[d] = 0.f;
     float m = -INFINITY, l = 0.f;
     for (int t = lane; t <= last; t += 64) {
-        const int pg = tab[t / p.P];
+        const int pg = min(max(tab[t / p.P], 0), p.num_pages - 1);   // never read outside the pool
         const size_t off = (size_t)pg * p.page_stride + kvh * p.head_stride + (t % p.P) * p.token_stride;
         const float* kp = p.k + off;
         const float* vp = p.v + off;
@@ -755,7 +762,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
         p.k = static_cast<const float*>(k_cache);
         p.v = static_cast<const float*>(v_cache);
         p.table = block_table; p.ctx = ctx_lens; p.out = static_cast<float*>(out);
-        p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.P = P; p.max_pages = max_pages_per_seq;
+        p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.P = P; p.max_pages = max_pages_per_seq; p.num_pages = num_pages;
         p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
         p.scale_log2 = scale * kLog2e;
         (void)hipGetLastError();
@@ -790,6 +797,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.v = static_cast<const uint16_t*>(v_cache);
     p.out = static_cast<uint16_t*>(out);
     p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.M = S * G; p.max_pages = max_pages_per_seq;
+    p.num_pages = num_pages;
     int NB;
     row_tiling(p.M, &NB, &p.RG);
     p.Mpad = 16 * NB;
