@@ -60,9 +60,16 @@ constexpr float kRescaleSlack = 12.0f;
 
 // ---- the tile list and its partition -------------------------------------------------------
 
+// The list is cut into slices of equal COST, not of equal tile count: besides its tiles every
+// sequence costs a wavefront about three tiles' worth of time (Q in, rows out; measured 8 us per
+// sequence part against 2.6 us per tile on the serving workload), so positions are counted in
+// "weights", tiles + kSeqCost per sequence.  A cut that falls into a sequence's extra weight is
+// moved to the end of that sequence.
+constexpr int kSeqCost = 3;
+
 struct TilePlan {     // static LDS of both kernels
-    int incl[256];    // inclusive prefix sums of the per-thread tile counts
-    int wave_sum[4];  // tiles counted by each of the block's four wavefronts
+    int incl[256];    // inclusive prefix sums of the per-thread sequence weights
+    int wave_sum[4];  // weight counted by each of the block's four wavefronts
 };
 
 // Copies one accumulation register to an ordinary vector register at exactly this point of the
@@ -90,16 +97,17 @@ __device__ __forceinline__ int seq_tiles(const AttnParams& p, const int32_t* __r
     return c > 0 ? (c + 31) >> 5 : 0;
 }
 
-// Block-wide inclusive scan of tile counts (thread t sums sequences [t*per, (t+1)*per)): a shuffle
-// scan inside each wavefront, then the wavefront totals through LDS - two barriers in all.
-// Returns the total number of tiles of one head.  Every thread of the block must call it.
+// Block-wide inclusive scan of sequence weights (thread t sums sequences [t*per, (t+1)*per)): a
+// shuffle scan inside each wavefront, then the wavefront totals through LDS - two barriers in all.
+// Returns the total weight of one head's list (its tiles + kSeqCost * B).  Every thread of the
+// block must call it.
 __device__ __forceinline__ int plan_scan(const AttnParams& p, const int32_t* __restrict__ ctx_lens, TilePlan& plan)
 {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int per = (p.B + 255) >> 8;
     const int b0 = tid * per, b1 = min(p.B, b0 + per);
     int x = 0;
-    for (int b = b0; b < b1; ++b) x += seq_tiles(p, ctx_lens, b);
+    for (int b = b0; b < b1; ++b) x += seq_tiles(p, ctx_lens, b) + kSeqCost;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         const int y = __shfl_up(x, off);
@@ -119,11 +127,11 @@ __device__ __forceinline__ int plan_scan(const AttnParams& p, const int32_t* __r
     return __builtin_amdgcn_readfirstlane(total);   // wave-uniform: keep it in a scalar register
 }
 
-// Sequence b that holds per-head tile position x (0 <= x < total) and the tiles before it.  A
-// wavefront-level lookup (after plan_scan): x must be the same in all lanes of the calling
-// wavefront, different wavefronts may look up different positions, nobody waits for anybody.
+// Sequence b whose weight range holds weight position y (0 <= y < total weight) and the weight
+// before it.  A wavefront-level lookup (after plan_scan): y must be the same in all lanes of the
+// calling wavefront, different wavefronts may look up different positions, nobody waits for anybody.
 __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* __restrict__ ctx_lens, const TilePlan& plan,
-                                            int x, int& b, int& pre)
+                                            int y, int& b, int& before)
 {
     const int lane = threadIdx.x & 63;
     int fb = 0, fpre = 0;
@@ -133,13 +141,13 @@ __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* 
         const int t = lane + 64 * k;
         const int incl = plan.incl[t];
         const int excl = t ? plan.incl[t - 1] : 0;
-        if (excl <= x && x < incl) {     // true for exactly one t of the 256
+        if (excl <= y && y < incl) {     // true for exactly one t of the 256
             const int per = (p.B + 255) >> 8;
             int bb = t * per, acc = excl;
             for (;;) {
-                const int nt = seq_tiles(p, ctx_lens, bb);
-                if (x < acc + nt) break;
-                acc += nt;
+                const int wgt = seq_tiles(p, ctx_lens, bb) + kSeqCost;
+                if (y < acc + wgt) break;
+                acc += wgt;
                 ++bb;
             }
             fb = bb;
@@ -152,7 +160,30 @@ __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* 
     const unsigned long long mask = __ballot(found);
     const int src = __builtin_amdgcn_readfirstlane((int)__ffsll((long long)mask) - 1);
     b = __builtin_amdgcn_readlane(fb, src);
-    pre = __builtin_amdgcn_readlane(fpre, src);
+    before = __builtin_amdgcn_readlane(fpre, src);
+}
+
+// First tile (position in the head's tile list) of slice j of Wg, the sequence b that holds it
+// and the tiles before b.  j >= Wg gives the end of the list (b and pre are then not set).
+// Wavefront-level like plan_locate.
+__device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32_t* __restrict__ ctx_lens, const TilePlan& plan,
+                                                int total_weight, int Wg, int j, int& b, int& pre)
+{
+    const int total_tiles = total_weight - kSeqCost * p.B;
+    if (j >= Wg) return total_tiles;
+    const int y = (int)((int64_t)total_weight * j / Wg);
+    int before;
+    plan_locate(p, ctx_lens, plan, y, b, before);
+    pre = before - kSeqCost * b;
+    int nt = seq_tiles(p, ctx_lens, b);
+    const int x = pre + min(y - before, nt);
+    // a cut at the end of a sequence belongs to the next sequence that has tiles
+    while (x >= pre + nt && x < total_tiles) {
+        pre += nt;
+        ++b;
+        nt = seq_tiles(p, ctx_lens, b);
+    }
+    return x;
 }
 
 // The block table and the context lengths are separate __restrict__ kernel arguments: nothing
@@ -174,23 +205,22 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     extern __shared__ u32x4 qlds_all[];   // [wavefront][(nb*4 + s)*64 + lane] Q operands of the current item
     __shared__ TilePlan plan;
 
-    const int total = plan_scan(p, ctx_lens, plan);
-    if (total == 0) return;
+    const int total_weight = plan_scan(p, ctx_lens, plan);
+    if (total_weight == kSeqCost * p.B) return;   // no tiles at all
     const int lane = threadIdx.x & 63;
     const int w = wave_id();
     const int NW = gridDim.x * 4;
     const int VH = p.Hkv * p.RG;
     const int Wg = NW >= VH ? NW / VH : 1;
     auto slice_of = [&](int v) { return NW >= VH ? v / VH : 0; };
-    auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
 
     const int wv = blockIdx.x * 4 + w;
     const int slice = slice_of(wv);
     if (slice >= Wg) return;
-    const int slice_begin = slice_start(slice), slice_end = slice_start(slice + 1);
+    int b0 = 0, pre0 = 0, b_end, pre_end;   // first sequence of the slice and the tiles before it
+    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, b0, pre0);
+    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, b_end, pre_end);
     if (slice_begin >= slice_end) return;
-    int b0, pre0;   // first sequence of the slice and the tiles before it
-    plan_locate(p, ctx_lens, plan, slice_begin, b0, pre0);
     const int vh0 = NW >= VH ? wv % VH : wv;
     const int vstep = NW >= VH ? VH : NW;
 
@@ -528,20 +558,24 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
                                                                   const int32_t* __restrict__ ctx_lens)
 {
     __shared__ TilePlan plan;
-    const int total = plan_scan(p, ctx_lens, plan);
+    const int total_weight = plan_scan(p, ctx_lens, plan);
+    const int total = total_weight - kSeqCost * p.B;
     if (total == 0) return;
     const int VH = p.Hkv * p.RG;
     const int vh = blockIdx.x % VH;
     const int jcut = blockIdx.x / VH + 1;          // cut = start of slice jcut
-    auto slice_start = [&](int j) { return (int)((int64_t)total * j / Wg); };
-    const int cut = slice_start(jcut);
+    auto slice_start = [&](int j) {
+        int bb, pp;
+        return slice_first_tile(p, ctx_lens, plan, total_weight, Wg, j, bb, pp);
+    };
+    int b = 0, pre = 0;
+    const int cut = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, jcut, b, pre);
     if (cut <= 0 || cut >= total) return;
-    int b, pre;
-    plan_locate(p, ctx_lens, plan, cut, b, pre);
     const int ntiles = seq_tiles(p, ctx_lens, b);
     if (cut == pre) return;                        // the cut coincides with the start of a sequence
     const int item_begin = pre, item_end = pre + ntiles;
-    if (slice_start(jcut - 1) > item_begin) return;   // an earlier cut is inside the same sequence
+    const int first_begin = slice_start(jcut - 1);
+    if (first_begin > item_begin) return;          // an earlier cut is inside the same sequence
     // slices jcut-1 .. hold this sequence's partials, written by wavefront j*VH + vh into slot 2v if
     // the sequence is the first one of that slice (the slice starts inside it), 2v+1 if it is its last
     auto slot_of = [&](int j, int jbeg) { return 2 * (j * VH + vh) + (jbeg >= item_begin ? 0 : 1); };
@@ -564,9 +598,12 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[nb][e] = 0.f;
     }
+    int knext = first_begin;                       // slice k is [kbeg, kend); slice jcut starts at the cut
     for (int k = jcut - 1; k < Wg; ++k) {
-        const int kbeg = slice_start(k), kend = slice_start(k + 1);
+        const int kbeg = knext;
         if (kbeg >= item_end) break;
+        const int kend = (k + 1 == jcut) ? cut : slice_start(k + 1);
+        knext = kend;
         if (kbeg == kend) continue;
         const size_t slot = (size_t)slot_of(k, kbeg);
         f32x4 ml[4];
