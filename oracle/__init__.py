@@ -51,6 +51,10 @@ def lib() -> C.CDLL:
         L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.isd_oracle_row_stats.restype = C.c_int
         L.isd_oracle_num_threads.restype = C.c_int
+        L.isd_oracle_accept_general.argtypes = [C.c_void_p] * 4 + [C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_double,
+                                                C.c_double, C.c_int32] + [C.c_void_p] * 7
+        L.isd_oracle_accept_general.restype = C.c_int
         L.isd_oracle_kv_append.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 7 + [C.c_int64] * 3 + [C.c_int32]
         L.isd_oracle_kv_append.restype = C.c_int
         L.isd_oracle_commit.argtypes = [C.c_void_p] * 8 + [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 6
@@ -214,3 +218,43 @@ def commit(state, accept_len, new_tokens, *, n_draft_steady, mask_token, P):
     if rc != 0:
         raise ValueError("isd_oracle_commit failed: %d" % rc)
     return int(status[0])
+
+
+def accept_general(logits, draft_tokens, rng_seed, *, n_draft, q_logits=None, q_row=None, greedy=None, rng_offset=0,
+                   temperature=1.0, tau=0.0, sample_proposals=False):
+    """Acceptance with general proposal distributions, temperature and relaxed threshold
+    (isd_oracle_accept_general).  q_logits [B,S,V] + q_row [B] give the proposal
+    distributions (None = point mass).  Returns the outputs of `accept` plus draft_q,
+    row_lse [B,S] and proposal_gap [B,S]."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, S, V = logits.shape
+    ncol = S - 1
+    dt = None
+    if S > 1:
+        dt = np.ascontiguousarray(np.ascontiguousarray(draft_tokens, dtype=np.int32)[:, :ncol])
+        assert dt.shape == (B, ncol)
+    ql = qr = None
+    if q_logits is not None:
+        ql = np.ascontiguousarray(q_logits, dtype=np.float32)
+        assert ql.shape == logits.shape
+        qr = np.ascontiguousarray(q_row, dtype=np.int32)
+        assert qr.shape == (B,)
+    nd_arr, nd_uni = None, 0
+    if np.isscalar(n_draft):
+        nd_uni = int(n_draft)
+    else:
+        nd_arr = np.ascontiguousarray(n_draft, dtype=np.int32)
+    g = None if greedy is None else np.ascontiguousarray(greedy, dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32)
+    new_tokens = np.zeros((B, S), dtype=np.int32)
+    probs = np.zeros((B, max(ncol, 0))); dq = np.zeros((B, max(ncol, 0))); margin = np.zeros((B, max(ncol, 0)))
+    lse = np.zeros((B, S)); gap = np.zeros(B); runner = np.zeros(B, dtype=np.int32); pgap = np.zeros((B, S))
+    rc = lib().isd_oracle_accept_general(_ptr(logits), _ptr(dt), _ptr(ql), _ptr(qr), int(rng_seed), _ptr(accept_len),
+                                         _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(g), int(rng_offset),
+                                         float(temperature), float(tau), 1 if sample_proposals else 0,
+                                         _ptr(probs) if ncol else None, _ptr(dq) if ncol else None, _ptr(lse),
+                                         _ptr(margin) if ncol else None, _ptr(gap), _ptr(runner), _ptr(pgap))
+    if rc != 0:
+        raise ValueError("isd_oracle_accept_general failed: %d" % rc)
+    return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, draft_q=dq, row_lse=lse,
+                accept_margin=margin, sample_gap=gap, runner_up=runner, proposal_gap=pgap)

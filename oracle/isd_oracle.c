@@ -15,6 +15,9 @@
  *     (arg-max) proposals as deployed in Sec. 3.3 (3): accept test, accepted
  *     prefix, resample from the residual on the first rejection, bonus token
  *     when every draft passes, arg-max proposals from the MASK rows.
+ *   - acceptance with general proposal distributions (Alg. 1 as printed: drafts
+ *     sampled from q, accept with probability min(1, p/q), residual
+ *     normalize(max(0, p - q))), sampling temperature and the relaxed threshold.
  *   - the counter-based generator Philox4x32-10 (Salmon et al., SC'11) that
  *     supplies the uniforms of the accept test and of the Gumbel-max sampler.
  *   - the two steps that close the loop between consecutive ISD steps (Sec. 3.3
@@ -322,6 +325,193 @@ int isd_oracle_accept(const float* logits, const int32_t* draft_tokens, uint64_t
             new_tokens[(int64_t)b * S + j] = tok;
         }
         free(m); free(Z); free(a);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Acceptance with general proposal distributions                            */
+/* ------------------------------------------------------------------------ */
+
+/* Gumbel noise of the proposal sampler: stream tag 2 of the same generator. */
+static double proposal_gumbel(uint64_t seed, uint32_t offset, uint32_t row, uint32_t i)
+{
+    double u = uniform_from_bits(rng_word(seed, offset, 2u, row, i));
+    return -log(-log(u));
+}
+
+/* log-sum-exp of row l / T (max subtracted first) and the lowest arg-max index */
+static void row_lse(const float* l, int V, double T, double* lse, int32_t* arg)
+{
+    double mx = -INFINITY;
+    int a = 0;
+    for (int i = 0; i < V; ++i)
+        if ((double)l[i] > mx) { mx = (double)l[i]; a = i; }
+    double z = 0.0;
+    for (int i = 0; i < V; ++i) z += exp(((double)l[i] - mx) / T);
+    *lse = mx / T + log(z);
+    *arg = a;
+}
+
+/*
+ * Alg. 1 in full: drafts x_j drawn from proposal distributions q_j, accepted with
+ * probability min(1, p_j(x_j)/q_j(x_j)), resampled from normalize(max(0, p_j - q_j)) at
+ * the first rejection (Sec. 3.2 "Adaptive stride via p/q acceptance"), with the two
+ * knobs the paper's runs use on top: sampling temperature T (App. H: all runs at
+ * T = 1, here any T > 0: p = softmax(l/T), q = softmax(l'/T)) and the relaxed
+ * threshold of Sec. 5 ("relaxing the acceptance threshold"): accept iff
+ * u < min(1, (1+tau) * p/q).
+ *
+ * q_logits == NULL is the deployed setting (point-mass proposals, q_j(x_j) = 1).
+ * Otherwise q_j = softmax(q_logits[b, q_row[b] + j, :] / T): the previous step's logits
+ * of the MASK row that proposed draft j.
+ *
+ * For sequence b with D drafts:
+ *   1. every row j: lse_j of l_j/T, arg-max a_j.
+ *   2. j < D: p_j = exp(l_j[x_j]/T - lse_j); q_j likewise from the q row (1 for point mass).
+ *   3. accept_j: greedy ? x_j == a_j : u_{b,j} < min(1, (1+tau) p_j/q_j)   (q_j = 0: accepted).
+ *   4. r = accepted prefix.
+ *   5. fresh token of row r: greedy: a_r.  Otherwise, after a rejection (r < D):
+ *        argmax_i [ln(p_r(i) - q_r(i)) + g_{b,r,i}] over i with p_r(i) > q_r(i)
+ *        (point mass: q_r = delta at x_r); a_r if no such i exists;
+ *      with all accepted (r = D): argmax_i [l_r[i]/T + g_{b,r,i}].
+ *   6. new_tokens: x_j (j < r) | fresh (j = r) | -1 (r < j <= D) | proposal (j > D):
+ *      sample_proposals ? argmax_i [l_j[i]/T + g2_{b,j,i}] (stream 2) : a_j.
+ * Outputs draft_probs (p_j), draft_q (q_j), row_lse [B,S]; diagnostics as in
+ * isd_oracle_accept, accept_margin = |u - min(1,(1+tau)p/q)|, plus proposal_gap [B,S]
+ * (top-two gap of the perturbed scores of every sampled proposal row, INFINITY elsewhere).
+ */
+int isd_oracle_accept_general(const float* logits, const int32_t* draft_tokens, const float* q_logits,
+                              const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len,
+                              int32_t* new_tokens, int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform,
+                              const int32_t* n_draft, const uint8_t* greedy, uint32_t rng_offset,
+                              double temperature, double tau, int32_t sample_proposals,
+                              double* draft_probs, double* draft_q, double* row_lse_out,
+                              double* accept_margin, double* sample_gap, int32_t* runner_up,
+                              double* proposal_gap)
+{
+    if (!logits || !accept_len || !new_tokens) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || V < 1 || !(temperature > 0.0) || !(tau >= 0.0)) return ORACLE_ERR_ARG;
+    if (S > 1 && !draft_tokens) return ORACLE_ERR_ARG;
+    if (q_logits && !q_row) return ORACLE_ERR_ARG;
+    const int ncol = S - 1;
+    const double T = temperature;
+    int status = ORACLE_OK;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int D = n_draft ? n_draft[b] : n_draft_uniform;
+        int bad = (D < 0 || D > S - 1);
+        if (!bad && q_logits && D > 0 && (q_row[b] < 0 || q_row[b] + D > S)) bad = 1;
+        for (int j = 0; !bad && j < D; ++j) {
+            const int x = draft_tokens[(int64_t)b * ncol + j];
+            if (x < 0 || x >= V) bad = 1;
+        }
+        if (bad) {
+#pragma omp critical
+            status = ORACLE_ERR_ARG;
+            continue;
+        }
+        const int is_greedy = greedy ? (greedy[b] != 0) : 0;
+        double* lse = (double*)malloc(sizeof(double) * S);
+        int32_t* a = (int32_t*)malloc(sizeof(int32_t) * S);
+        for (int j = 0; j < S; ++j) {
+            row_lse(logits + ((int64_t)b * S + j) * V, V, T, &lse[j], &a[j]);
+            if (row_lse_out) row_lse_out[(int64_t)b * S + j] = lse[j];
+        }
+        for (int j = 0; j < ncol; ++j) {
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = 0.0;
+            if (draft_q) draft_q[(int64_t)b * ncol + j] = 0.0;
+            if (accept_margin) accept_margin[(int64_t)b * ncol + j] = INFINITY;
+        }
+        int r = D, open = 1;
+        for (int j = 0; j < D; ++j) {
+            const float* l = logits + ((int64_t)b * S + j) * V;
+            const int x = draft_tokens[(int64_t)b * ncol + j];
+            const double p = exp((double)l[x] / T - lse[j]);
+            double q = 1.0;
+            if (q_logits) {
+                const float* lq = q_logits + ((int64_t)b * S + q_row[b] + j) * V;
+                double lse_q;
+                int32_t aq;
+                row_lse(lq, V, T, &lse_q, &aq);
+                q = exp((double)lq[x] / T - lse_q);
+            }
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = p;
+            if (draft_q) draft_q[(int64_t)b * ncol + j] = q;
+            int ok;
+            if (is_greedy) {
+                ok = (x == a[j]);
+            } else {
+                const double u = isd_oracle_accept_uniform(rng_seed, rng_offset, (uint32_t)(b * S + j));
+                double thr = (q > 0.0) ? (1.0 + tau) * p / q : INFINITY;
+                if (thr > 1.0) thr = 1.0;
+                ok = (u < thr);
+                if (accept_margin) accept_margin[(int64_t)b * ncol + j] = fabs(u - thr);
+            }
+            if (open && !ok) { r = j; open = 0; }
+        }
+        accept_len[b] = r;
+
+        int fresh;
+        double gap = INFINITY;
+        int second = -1;
+        if (is_greedy) {
+            fresh = a[r];
+        } else {
+            const float* l = logits + ((int64_t)b * S + r) * V;
+            const uint32_t row = (uint32_t)(b * S + r);
+            double best = -INFINITY, next = -INFINITY;
+            fresh = -1;
+            if (r < D) {
+                const int x = draft_tokens[(int64_t)b * ncol + r];
+                const float* lq = q_logits ? q_logits + ((int64_t)b * S + q_row[b] + r) * V : NULL;
+                double lse_q = 0.0;
+                int32_t aq;
+                if (lq) row_lse(lq, V, T, &lse_q, &aq);
+                for (int i = 0; i < V; ++i) {
+                    const double pi = exp((double)l[i] / T - lse[r]);
+                    const double qi = lq ? exp((double)lq[i] / T - lse_q) : (i == x ? 1.0 : 0.0);
+                    if (!(pi > qi)) continue;
+                    const double sc = log(pi - qi) + isd_oracle_gumbel(rng_seed, rng_offset, row, (uint32_t)i);
+                    if (sc > best) { next = best; second = fresh; best = sc; fresh = i; }
+                    else if (sc > next) { next = sc; second = i; }
+                }
+                if (fresh < 0) { fresh = a[r]; best = INFINITY; }
+            } else {
+                for (int i = 0; i < V; ++i) {
+                    const double sc = (double)l[i] / T + isd_oracle_gumbel(rng_seed, rng_offset, row, (uint32_t)i);
+                    if (sc > best) { next = best; second = fresh; best = sc; fresh = i; }
+                    else if (sc > next) { next = sc; second = i; }
+                }
+            }
+            gap = best - next;
+        }
+        if (sample_gap) sample_gap[b] = gap;
+        if (runner_up) runner_up[b] = second;
+
+        for (int j = 0; j < S; ++j) {
+            int32_t tok;
+            double pg = INFINITY;
+            if (j < r) tok = draft_tokens[(int64_t)b * ncol + j];
+            else if (j == r) tok = fresh;
+            else if (j <= D) tok = -1;
+            else if (!sample_proposals || is_greedy) tok = a[j];
+            else {
+                const float* l = logits + ((int64_t)b * S + j) * V;
+                double best = -INFINITY, next = -INFINITY;
+                tok = -1;
+                for (int i = 0; i < V; ++i) {
+                    const double sc = (double)l[i] / T + proposal_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + j), (uint32_t)i);
+                    if (sc > best) { next = best; best = sc; tok = i; }
+                    else if (sc > next) next = sc;
+                }
+                pg = best - next;
+            }
+            new_tokens[(int64_t)b * S + j] = tok;
+            if (proposal_gap) proposal_gap[(int64_t)b * S + j] = pg;
+        }
+        free(lse); free(a);
     }
     return status;
 }
