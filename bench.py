@@ -295,6 +295,29 @@ def main():
     }
     del states
 
+    # the general acceptance entry point (proposal distributions, temperature, relaxed threshold,
+    # sampled proposals) on the same logits; the proposal logits are a second buffer of the same size
+    gen = None
+    if S > 1:
+        ws_gen = torch.empty(max(256, idlm.idlm_isd_accept_general_workspace(B, S, V)), dtype=torch.uint8, device=dev)
+        q_logits = acc.logits.flip(1).contiguous()
+        q_row = torch.full((B,), S - 1 - int(acc.n_draft.max().item()), dtype=torch.int32, device=dev)
+        q_lse = torch.empty(B, S, dtype=torch.float32, device=dev)
+        idlm.idlm_isd_accept_general(q_logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=0, greedy=acc.greedy,
+                                     temperature=0.9, row_lse=q_lse, workspace=ws_gen)
+
+        def general(**kw):
+            return timed(lambda: idlm.idlm_isd_accept_general(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens,
+                                                              n_draft=acc.n_draft, greedy=acc.greedy, workspace=ws_gen,
+                                                              **kw), n=5)
+        gen = {"point_mass_ms": general(),
+               "proposal_distributions_ms": general(q_logits=q_logits, q_row=q_row, q_lse=q_lse, temperature=0.9, tau=0.1),
+               "proposal_distributions_without_kept_lse_ms": general(q_logits=q_logits, q_row=q_row, temperature=0.9,
+                                                                      tau=0.1),
+               "with_sampled_proposals_ms": general(q_logits=q_logits, q_row=q_row, q_lse=q_lse, temperature=0.9,
+                                                    tau=0.1, sample_proposals=True)}
+        del q_logits, ws_gen
+
     cpu = None
     if args.cpu_sample > 0 and cfg.dtype == "bf16":
         cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
@@ -323,6 +346,7 @@ def main():
         "stream_ceiling": stream_probe,
         "between_steps": loop_kernels,
         "launch_modes": launch_modes,
+        "accept_general": gen,
         "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
                           "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }

@@ -167,6 +167,45 @@ int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
 
 /*
+ * idlm_isd_accept_general - acceptance with general proposal distributions, sampling
+ * temperature, relaxed threshold and sampled proposals: Alg. 1 as printed (drafts drawn from
+ * q_j, accepted with probability min(1, p_j(x_j)/q_j(x_j)), resampled from
+ * normalize(max(0, p_j - q_j)) at the first rejection, Sec. 3.2 "Adaptive stride via p/q
+ * acceptance"), the threshold relaxation discussed in Sec. 5 (accept iff
+ * u < min(1, (1+tau) p/q)) and a sampling temperature T (App. H lists the sampling set-up of
+ * the paper's runs): p_j = softmax(logits[b,j,:]/T), q_j = softmax(q_logits[b, q_row[b]+j, :]/T).
+ * idlm_isd_accept is the deployed special case (point-mass proposals, T = 1, tau = 0) and the
+ * one to use on the hot path; outputs and conventions are the same, with these additions:
+ *
+ * q_logits     fp32 [B,S,V] or NULL: the logits of the step that proposed the drafts (the
+ *              caller keeps the previous step's buffer); NULL = point-mass proposals, q = 1.
+ * q_row        int32 [B] (required with q_logits): row of q_logits that proposed draft 0 of
+ *              sequence b; draft j came from row q_row[b]+j (forced into the sequence).
+ * q_lse        fp32 [B,S] or NULL: natural-log sum of exp(q_logits[b,i,:]/T) per row - the
+ *              row_lse output of the call that processed q_logits at the same T.  NULL with
+ *              q_logits given costs one more streaming pass over q_logits.
+ * temperature  T > 0.  tau >= 0.
+ * sample_proposals  non-zero: rows after the drafts propose argmax_i(l_i/T + Gumbel noise of
+ *              random stream 2) instead of the arg-max (greedy sequences always use the arg-max).
+ * fresh token  after a rejection: argmax_i [ln(p(i) - q(i)) + g_i] over i with p(i) > q(i)
+ *              (point mass: q = delta at the draft), the row's arg-max if there is no such i;
+ *              with every draft accepted: argmax_i [l_i/T + g_i] (random stream 1).
+ * draft_probs  fp32 [B,S-1] out or NULL: p_j(x_j);  draft_q: q_j(x_j) (1 for point mass).
+ * row_lse      fp32 [B,S] out or NULL.
+ * workspace    at least idlm_isd_accept_general_workspace(B,S,V) bytes, 256-byte aligned.
+ * Same shape limits as idlm_isd_accept.
+ */
+int idlm_isd_accept_general(const float* logits, const int32_t* draft_tokens, const float* q_logits,
+                            const int32_t* q_row, const float* q_lse, uint64_t rng_seed,
+                            int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                            int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                            uint32_t rng_offset, float temperature, float tau, int32_t sample_proposals,
+                            float* draft_probs, float* draft_q, float* row_lse, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+size_t idlm_isd_accept_general_workspace(int32_t B, int32_t S, int32_t V);
+
+/*
  * idlm_isd_kv_append - batched scatter of the stride's K/V rows into the paged cache, before the
  * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): "KV slots
  * are allocated via a single batched scatter").

@@ -49,6 +49,11 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_ev.restype = C.c_int
         L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_workspace.restype = C.c_size_t
+        L.idlm_isd_accept_general.argtypes = [vp, vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp,
+                                              C.c_uint32, C.c_float, C.c_float, i32, vp, vp, vp, vp, C.c_size_t, vp]
+        L.idlm_isd_accept_general.restype = C.c_int
+        L.idlm_isd_accept_general_workspace.argtypes = [i32, i32, i32]
+        L.idlm_isd_accept_general_workspace.restype = C.c_size_t
         L.idlm_isd_kv_append.argtypes = [vp] * 6 + [i32] * 7 + [i64] * 3 + [i32, vp]
         L.idlm_isd_kv_append.restype = C.c_int
         L.idlm_isd_commit.argtypes = [vp] * 8 + [i32] + [vp] * 5 + [i32] * 6 + [vp]
@@ -218,3 +223,36 @@ def idlm_isd_commit(accept_len, new_tokens, state, *, n_draft_steady, mask_token
                                B, S, P, state["block_table"].shape[1], _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_commit")
+
+
+def idlm_isd_accept_general_workspace(B, S, V) -> int:
+    return int(lib().idlm_isd_accept_general_workspace(B, S, V))
+
+
+def idlm_isd_accept_general(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, q_logits=None,
+                            q_row=None, q_lse=None, greedy=None, rng_offset=0, temperature=1.0, tau=0.0,
+                            sample_proposals=False, draft_probs=None, draft_q=None, row_lse=None, workspace=None,
+                            stream=None):
+    """Acceptance with general proposal distributions, temperature and relaxed threshold (see idlm.h)."""
+    B, S, V = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    if S > 1:
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, S - 1) and draft_tokens.is_contiguous()
+    if q_logits is not None:
+        assert q_logits.shape == logits.shape and q_logits.dtype == torch.float32 and q_logits.is_contiguous()
+        assert q_row is not None and q_row.dtype == torch.int32 and q_row.shape == (B,)
+    if q_lse is not None:
+        assert q_lse.dtype == torch.float32 and q_lse.shape == (B, S) and q_lse.is_contiguous()
+    nd_uni, nd_arr = (int(n_draft), None) if isinstance(n_draft, int) else (0, n_draft)
+    if nd_arr is not None:
+        assert nd_arr.dtype == torch.int32 and nd_arr.shape == (B,)
+    for t, shape in ((draft_probs, (B, S - 1)), (draft_q, (B, S - 1)), (row_lse, (B, S))):
+        if t is not None:
+            assert t.dtype == torch.float32 and tuple(t.shape) == shape and t.is_contiguous()
+    rc = lib().idlm_isd_accept_general(
+        _ptr(logits), _ptr(draft_tokens) if S > 1 else None, _ptr(q_logits), _ptr(q_row), _ptr(q_lse), int(rng_seed),
+        _ptr(accept_len), _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(greedy), int(rng_offset),
+        float(temperature), float(tau), 1 if sample_proposals else 0, _ptr(draft_probs), _ptr(draft_q), _ptr(row_lse),
+        _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_accept_general")

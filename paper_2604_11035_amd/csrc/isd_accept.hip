@@ -7,60 +7,9 @@
 //      fresh token, split over several workgroups that combine with one 64-bit atomic max;
 //   4. decode of the winning keys into new_tokens.
 // HBM-bound: the algorithmic traffic is one read of the logits (4*V bytes per row).
-#include "idlm_common.h"
-#include <limits.h>
+#include "isd_accept_common.h"
 
 namespace idlm {
-
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-struct RowPartial {   // statistics of one slice of one logit row
-    float m;          // maximum (true value, compared exactly)
-    float z;          // sum of 2^(l*log2e - ref_log2(m))
-    int arg;          // lowest index attaining m (INT_MAX if the slice is empty)
-    int pad;
-};
-
-// Best (score, index) of a sampled row as one 64-bit key whose unsigned order is "higher score
-// first, then lower index": workgroups of a row combine with a single atomic max, no fences.
-__device__ __forceinline__ unsigned long long sample_key(float score, int idx)
-{
-    const uint32_t bits = __float_as_uint(score);
-    const uint32_t ordered = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-    return ((unsigned long long)ordered << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)idx);
-}
-
-struct AcceptPlan {
-    int chunk;    // vocabulary elements per workgroup in pass 1 (multiple of 1024)
-    int nsplit;   // slices per row in pass 1
-    int gchunk;   // vocabulary elements per workgroup in the Gumbel pass (multiple of 1024)
-    int nsb;      // workgroups per sequence in pass 2
-};
-
-static AcceptPlan make_plan(int32_t B, int32_t S, int32_t V)
-{
-    AcceptPlan p;
-    const int64_t rows = (int64_t)B * S;
-    // A workgroup streams a whole row when there are enough rows to fill the chip (every extra
-    // slice costs a block reduction and a launch slot: whole rows measured 6.5 TB/s, 128 KB
-    // slices 5.7 TB/s on B*S = 4096 rows); fewer rows are cut into slices of at least 4K
-    // elements until about 4096 workgroups exist.
-    int64_t nsplit = (4096 + rows - 1) / (rows > 0 ? rows : 1);
-    int64_t max_split = ((int64_t)V + 4095) / 4096;
-    if (nsplit > max_split) nsplit = max_split;
-    if (nsplit < 1) nsplit = 1;
-    int64_t chunk = (((int64_t)V + nsplit - 1) / nsplit + 1023) / 1024 * 1024;
-    p.chunk = (int)chunk;
-    p.nsplit = (int)(((int64_t)V + chunk - 1) / chunk);
-    int64_t nsb = ((int64_t)V + 4095) / 4096;     // 4K elements of Philox + logs per workgroup
-    if (nsb > 64) nsb = 64;
-    int64_t gchunk = (((int64_t)V + nsb - 1) / nsb + 1023) / 1024 * 1024;
-    p.gchunk = (int)gchunk;
-    p.nsb = (int)(((int64_t)V + gchunk - 1) / gchunk);
-    return p;
-}
-
-static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct AcceptWorkspace {
     size_t stats_off, keys_off, chain_off, total;
@@ -75,138 +24,6 @@ static AcceptWorkspace layout(int32_t B, int32_t S, const AcceptPlan& p)
     w.chain_off = w.keys_off + align256((size_t)B * sizeof(unsigned long long));   // one arg-max key per sequence
     w.total = w.chain_off + align256((size_t)B * 2 * sizeof(int32_t));
     return w;
-}
-
-// ---- reductions ---------------------------------------------------------------------------
-
-__device__ __forceinline__ void combine_stats(float& m, float& z, int& a, float m2, float z2, int a2)
-{
-    const float mm = fmaxf(m, m2);
-    const float r = ref_log2(mm);
-    z = z * rescale_factor(m, r) + z2 * rescale_factor(m2, r);
-    a = (m2 > m) ? a2 : ((m > m2) ? a : min(a, a2));
-    m = mm;
-}
-
-__device__ __forceinline__ void combine_best(float& s, int& i, float s2, int i2)
-{
-    if (s2 > s || (s2 == s && i2 < i)) { s = s2; i = i2; }
-}
-
-// ---- pass 1: row statistics ---------------------------------------------------------------
-
-template <int UNROLL>
-__global__ __launch_bounds__(256) void isd_row_stats_kernel(const float* __restrict__ logits, int V,
-                                                            int chunk, int nsplit, int S,
-                                                            RowPartial* __restrict__ stats)
-{
-    const int row = blockIdx.x / nsplit;
-    const int c = blockIdx.x - row * nsplit;
-    const int tid = threadIdx.x;
-    const f32x4* __restrict__ p4 = reinterpret_cast<const f32x4*>(logits + (size_t)row * V);
-    const int fbeg = (c * chunk) >> 2;
-    const int fend = min(V, (c + 1) * chunk) >> 2;
-
-
-    float m = -INFINITY;   // running maximum of this thread's elements
-    float z = 0.f;         // sum of 2^(l*log2e - ref_log2(m))
-    int arg4 = -1;         // float4 index that holds the first occurrence of m
-
-    int f = fbeg + tid;
-    for (; f + (UNROLL - 1) * 256 < fend; f += UNROLL * 256) {
-        f32x4 v[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(p4 + f + u * 256);
-        float newm = m;
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const float bm = fmaxf(fmaxf(v[u].x, v[u].y), fmaxf(v[u].z, v[u].w));
-            if (bm > newm) { newm = bm; arg4 = f + u * 256; }
-        }
-        const float r = ref_log2(newm);
-        float acc = z * rescale_factor(m, r);
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            acc += fast_exp2(fmaf(v[u].x, kLog2e, -r));
-            acc += fast_exp2(fmaf(v[u].y, kLog2e, -r));
-            acc += fast_exp2(fmaf(v[u].z, kLog2e, -r));
-            acc += fast_exp2(fmaf(v[u].w, kLog2e, -r));
-        }
-        z = acc;
-        m = newm;
-    }
-    for (; f < fend; f += 256) {
-        const f32x4 v = __builtin_nontemporal_load(p4 + f);
-        const float bm = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
-        float newm = m;
-        if (bm > newm) { newm = bm; arg4 = f; }
-        const float r = ref_log2(newm);
-        float acc = z * rescale_factor(m, r);
-        acc += fast_exp2(fmaf(v.x, kLog2e, -r));
-        acc += fast_exp2(fmaf(v.y, kLog2e, -r));
-        acc += fast_exp2(fmaf(v.z, kLog2e, -r));
-        acc += fast_exp2(fmaf(v.w, kLog2e, -r));
-        z = acc;
-        m = newm;
-    }
-
-    // which of the four components was first to reach m
-    int arg = INT_MAX;
-    if (arg4 >= 0) {
-        const f32x4 v = p4[arg4];
-        const int lane = (v.x == m) ? 0 : (v.y == m) ? 1 : (v.z == m) ? 2 : 3;
-        arg = arg4 * 4 + lane;
-    }
-
-    // wavefront reduction, then the four wavefronts through LDS
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const float m2 = __shfl_xor(m, off);
-        const float z2 = __shfl_xor(z, off);
-        const int a2 = __shfl_xor(arg, off);
-        combine_stats(m, z, arg, m2, z2, a2);
-    }
-    __shared__ float sm[4], sz[4];
-    __shared__ int sa[4];
-    const int w = tid >> 6;
-    if ((tid & 63) == 0) { sm[w] = m; sz[w] = z; sa[w] = arg; }
-    __syncthreads();
-    if (tid == 0) {
-        for (int k = 1; k < 4; ++k) combine_stats(m, z, arg, sm[k], sz[k], sa[k]);
-        RowPartial out;
-        out.m = m; out.z = z; out.arg = arg; out.pad = 0;
-        stats[(size_t)row * nsplit + c] = out;
-    }
-}
-
-// ---- counter-based random numbers (Philox4x32-10, Salmon et al. SC'11) --------------------
-
-__device__ __forceinline__ uint4 philox4x32_10(uint4 ctr, uint2 key)
-{
-#pragma unroll
-    for (int round = 0; round < 10; ++round) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, ctr.x), lo0 = 0xD2511F53u * ctr.x;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, ctr.z), lo1 = 0xCD9E8D57u * ctr.z;
-        ctr = make_uint4(hi1 ^ ctr.y ^ key.x, lo1, hi0 ^ ctr.w ^ key.y, lo0);
-        key.x += 0x9E3779B9u;
-        key.y += 0xBB67AE85u;
-    }
-    return ctr;
-}
-
-// 32 bits -> u = (2*(x>>9)+1) * 2^-24: an odd 24-bit numerator, exact in fp32, inside (0,1)
-__device__ __forceinline__ float unit_uniform(uint32_t x)
-{
-    return (float)(2u * (x >> 9) + 1u) * 5.9604644775390625e-8f;
-}
-
-// g = -ln(-ln u).  The inner logarithm must be accurate relative to its result for u close to 1
-// (the large noise values that decide the arg-max), so it is the library logf; the outer one only
-// needs absolute accuracy and is the hardware log2.
-__device__ __forceinline__ float gumbel(uint32_t x)
-{
-    const float t = -logf(unit_uniform(x));
-    return -0.69314718056f * __builtin_amdgcn_logf(t);
 }
 
 // ---- pass 2: accept chain and proposals, one wavefront per sequence ---------------------------
@@ -377,7 +194,7 @@ extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_toke
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     hipLaunchKernelGGL(isd_row_stats_kernel<16>, dim3((unsigned)(B * S * plan.nsplit)), dim3(256), 0, st,
-                       logits, V, plan.chunk, plan.nsplit, S, stats);
+                       logits, V, plan.chunk, plan.nsplit, S, stats, kLog2e);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const uint2 key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
     ChainResult* chain = reinterpret_cast<ChainResult*>(ws + w.chain_off);

@@ -1,0 +1,135 @@
+"""GPU parity of idlm_isd_accept_general (general proposal distributions, temperature, relaxed
+threshold, sampled proposals) with the CPU oracle, through the C ABI.  Integer outputs are
+compared bit for bit wherever the oracle's decision margins say that single precision cannot
+flip the decision; the skipped decisions are counted and must stay rare."""
+import numpy as np
+import pytest
+import torch
+from scipy.special import softmax
+
+import oracle
+import paper_2604_11035_amd as idlm
+from helpers import ACCEPT_MARGIN, GAP_MARGIN, PROB_ABS_TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RESID_GAP_MARGIN = 2e-3      # ln(p - q) loses digits where p is close to q
+
+
+def make_case(rng, B, S, V, T, corr):
+    logits = (rng.standard_normal((B, S, V)) * 3).astype(np.float32)
+    q_logits = (corr * logits[:, ::-1] + (1 - corr) * rng.standard_normal((B, S, V)) * 3).astype(np.float32)
+    n_draft = rng.integers(0, S, size=B).astype(np.int32)
+    q_row = np.array([rng.integers(0, S - d + 1) for d in n_draft], dtype=np.int32)
+    drafts = np.zeros((B, S - 1), np.int32)
+    for b in range(B):
+        for j in range(n_draft[b]):
+            # the proposal distribution of draft j, blended towards the anchor so that a fair share is accepted
+            lq = q_logits[b, q_row[b] + j]
+            lq[:] = 0.6 * logits[b, j] + 0.4 * lq
+            drafts[b, j] = rng.choice(V, p=softmax(lq.astype(np.float64) / T))
+    greedy = (rng.random(B) < 0.25).astype(np.uint8)
+    return logits, q_logits, q_row, drafts, n_draft, greedy
+
+
+def run_gpu(logits, drafts, n_draft, greedy, seed, off, T, tau, samp, q_logits=None, q_row=None, q_lse=None):
+    B, S, V = logits.shape
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    accept_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    new_tokens = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+    probs = torch.full((B, S - 1), -7.0, device=DEV); dq = torch.full((B, S - 1), -7.0, device=DEV)
+    lse = torch.full((B, S), -7.0, device=DEV)
+    ws = torch.empty(max(256, idlm.idlm_isd_accept_general_workspace(B, S, V)), dtype=torch.uint8, device=DEV)
+    idlm.idlm_isd_accept_general(t(logits), t(drafts), seed, accept_len, new_tokens, n_draft=t(n_draft), q_logits=t(q_logits),
+                                 q_row=t(q_row), q_lse=q_lse, greedy=t(greedy), rng_offset=off, temperature=T, tau=tau,
+                                 sample_proposals=samp, draft_probs=probs, draft_q=dq, row_lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    return dict(accept_len=accept_len.cpu().numpy(), new_tokens=new_tokens.cpu().numpy(), draft_probs=probs.cpu().numpy(),
+                draft_q=dq.cpu().numpy(), row_lse=lse.cpu().numpy(), row_lse_dev=lse)
+
+
+def compare(g, r, n_draft, greedy, general_q):
+    B, S = g["new_tokens"].shape
+    assert np.abs(g["draft_probs"] - r["draft_probs"]).max() <= PROB_ABS_TOL
+    assert np.abs(g["draft_q"] - r["draft_q"]).max() <= PROB_ABS_TOL
+    assert np.abs(g["row_lse"] - r["row_lse"]).max() <= 2e-5 * max(1.0, np.abs(r["row_lse"]).max())
+    skipped = 0
+    for b in range(B):
+        D = n_draft[b]
+        decisive = r["accept_margin"][b, :min(D, r["accept_len"][b] + 1)]
+        if (decisive < ACCEPT_MARGIN).any():
+            skipped += 1
+            continue
+        assert g["accept_len"][b] == r["accept_len"][b], b
+        rr = r["accept_len"][b]
+        for j in range(S):
+            got, want = g["new_tokens"][b, j], r["new_tokens"][b, j]
+            if j == rr and not greedy[b]:
+                margin = RESID_GAP_MARGIN if (general_q and rr < D) else GAP_MARGIN
+                if got != want:
+                    assert r["sample_gap"][b] < margin and got == r["runner_up"][b], (b, j, got, want, r["sample_gap"][b])
+                    skipped += 1
+            elif j > D and np.isfinite(r["proposal_gap"][b, j]):
+                if got != want:
+                    assert r["proposal_gap"][b, j] < GAP_MARGIN, (b, j)
+                    skipped += 1
+            else:
+                assert got == want, (b, j, got, want)
+    return skipped
+
+
+def test_point_mass_setting_equals_the_fast_path_and_the_oracle():
+    rng = np.random.default_rng(1)
+    B, S, V = 40, 8, 8192
+    logits, _, _, drafts, n_draft, greedy = make_case(rng, B, S, V, 1.0, 0.5)
+    drafts = np.where(rng.random((B, S - 1)) < 0.6, logits[:, :S - 1].argmax(-1), drafts).astype(np.int32)
+    g = run_gpu(logits, drafts, n_draft, greedy, 99, 4, 1.0, 0.0, False)
+    r = oracle.accept_general(logits, drafts, 99, n_draft=n_draft, greedy=greedy, rng_offset=4)
+    assert compare(g, r, n_draft, greedy, False) <= 1
+    # the deployed entry point gives the same tokens
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    al = torch.empty(B, dtype=torch.int32, device=DEV); nt = torch.empty(B, S, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=DEV)
+    idlm.idlm_isd_accept(t(logits), t(drafts), 99, al, nt, n_draft=t(n_draft), greedy=t(greedy), rng_offset=4, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(al.cpu().numpy(), g["accept_len"]) and np.array_equal(nt.cpu().numpy(), g["new_tokens"])
+
+
+@pytest.mark.parametrize("T,tau,samp", [(1.0, 0.0, False), (0.8, 0.0, True), (1.5, 0.3, False), (1.0, 0.5, True)])
+def test_general_proposals_match_the_oracle(T, tau, samp):
+    rng = np.random.default_rng(int(T * 100 + tau * 10 + samp))
+    B, S, V = 48, 8, 4096
+    logits, q_logits, q_row, drafts, n_draft, greedy = make_case(rng, B, S, V, T, 0.3)
+    r = oracle.accept_general(logits, drafts, 5, n_draft=n_draft, q_logits=q_logits, q_row=q_row, greedy=greedy,
+                              rng_offset=2, temperature=T, tau=tau, sample_proposals=samp)
+    # (a) the library computes the proposal rows' log-sum-exp itself
+    g = run_gpu(logits, drafts, n_draft, greedy, 5, 2, T, tau, samp, q_logits, q_row)
+    skipped = compare(g, r, n_draft, greedy, True)
+    # (b) the caller kept it from the call that processed those logits (here: a call on q_logits)
+    prev = run_gpu(q_logits, drafts, np.zeros(B, np.int32), greedy, 1, 0, T, 0.0, False)
+    g2 = run_gpu(logits, drafts, n_draft, greedy, 5, 2, T, tau, samp, q_logits, q_row, q_lse=prev["row_lse_dev"])
+    skipped += compare(g2, r, n_draft, greedy, True)
+    assert skipped <= 4
+    rej = (r["accept_len"] < n_draft) & (greedy == 0)
+    assert rej.sum() >= 5 and ((r["accept_len"] == n_draft) & (n_draft > 0)).sum() >= 5      # both branches exercised
+
+
+def test_large_ragged_vocabulary_and_single_row():
+    rng = np.random.default_rng(12)
+    B, S, V, T = 6, 4, 151936, 1.2
+    logits, q_logits, q_row, drafts, n_draft, greedy = make_case(rng, B, S, V, T, 0.2)
+    greedy[:] = 0
+    r = oracle.accept_general(logits, drafts, 8, n_draft=n_draft, q_logits=q_logits, q_row=q_row, greedy=greedy,
+                              temperature=T, tau=0.1, sample_proposals=True)
+    g = run_gpu(logits, drafts, n_draft, greedy, 8, 0, T, 0.1, True, q_logits, q_row)
+    assert compare(g, r, n_draft, greedy, True) <= 1
+    # S = 1: nothing to verify, one sampled token per sequence
+    l1 = (rng.standard_normal((5, 1, 33000)) * 2).astype(np.float32)
+    z = np.zeros(5, np.int32)
+    r1 = oracle.accept_general(l1, None, 3, n_draft=z, temperature=0.9)
+    t = lambda a: torch.from_numpy(a).to(DEV)
+    al = torch.empty(5, dtype=torch.int32, device=DEV); nt = torch.empty(5, 1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(256, idlm.idlm_isd_accept_general_workspace(5, 1, 33000)), dtype=torch.uint8, device=DEV)
+    idlm.idlm_isd_accept_general(t(l1), None, 3, al, nt, n_draft=t(z), temperature=0.9, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(nt.cpu().numpy(), r1["new_tokens"]) and (al.cpu().numpy() == 0).all()
