@@ -160,3 +160,32 @@ def test_commit_rejects_bad_arguments(kw, code):
 
 def test_commit_empty_batch_is_ok_without_device():
     assert _commit(B=0) == 0
+
+
+def _general(**kw):
+    a = dict(logits=FAKE, drafts=FAKE, ql=None, qrow=None, qlse=None, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024,
+             ndu=1, nd=None, greedy=None, off=0, T=1.0, tau=0.0, samp=0, probs=None, dq=None, lse=None, ws=None,
+             ws_bytes=0, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_accept_general(a["logits"], a["drafts"], a["ql"], a["qrow"], a["qlse"], a["seed"],
+                                              a["alen"], a["toks"], a["B"], a["S"], a["V"], a["ndu"], a["nd"],
+                                              a["greedy"], a["off"], a["T"], a["tau"], a["samp"], a["probs"], a["dq"],
+                                              a["lse"], a["ws"], a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(logits=None), -1), (dict(toks=None), -1), (dict(drafts=None), -1), (dict(ql=FAKE), -1),   # q_logits without q_row
+    (dict(S=0), -2), (dict(V=1022), -2), (dict(ndu=4), -2), (dict(T=0.0), -2), (dict(T=-1.0), -2), (dict(tau=-0.5), -2),
+    (dict(T=float("inf")), -2), (dict(T=float("nan")), -2),
+    (dict(logits=ODD), -4), (dict(ql=ODD, qrow=FAKE), -4),
+    (dict(), -5), (dict(ws=FAKE, ws_bytes=64), -5),
+])
+def test_general_accept_rejects_bad_arguments(kw, code):
+    assert _general(**kw) == code
+
+
+def test_general_accept_workspace_and_empty_batch():
+    assert _general(B=0) == 0
+    g = idlm.idlm_isd_accept_general_workspace(256, 16, 151936)
+    assert g > idlm.idlm_isd_accept_workspace(256, 16, 151936) and g % 256 == 0
+    assert idlm.idlm_isd_accept_general_workspace(4, 4, 1023) == 0
