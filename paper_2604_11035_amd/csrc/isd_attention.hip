@@ -826,6 +826,14 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             return IDLM_ERR_LAUNCH;
         W = cus > kMaxWorkgroups ? kMaxWorkgroups : cus;
+        // A batch that cannot hold more than a few tiles per wavefront gets a smaller grid: slices
+        // shorter than about 16 tiles only multiply the partial results that have to be joined.  The
+        // bound uses what the host knows (B and the width of the block table).
+        int nb_, rg_;
+        row_tiling(S * G, &nb_, &rg_);
+        const int64_t max_tiles = (int64_t)B * ((max_pages_per_seq + 1) / 2);
+        const int64_t wavefronts = (max_tiles / 16 > 0 ? max_tiles / 16 : 1) * Hkv * rg_;
+        if ((wavefronts + 3) / 4 < W) W = (int)((wavefronts + 3) / 4);
     }
 
     AttnParams p;
