@@ -55,6 +55,10 @@ def lib() -> C.CDLL:
                                                 C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_double,
                                                 C.c_double, C.c_int32] + [C.c_void_p] * 7
         L.isd_oracle_accept_general.restype = C.c_int
+        L.isd_oracle_accept_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32,
+                                                 C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                                 C.c_double, C.c_double, C.c_int32, C.c_double, C.c_int32] + [C.c_void_p] * 6
+        L.isd_oracle_accept_filtered.restype = C.c_int
         L.isd_oracle_kv_append.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 7 + [C.c_int64] * 3 + [C.c_int32]
         L.isd_oracle_kv_append.restype = C.c_int
         L.isd_oracle_commit.argtypes = [C.c_void_p] * 8 + [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 6
@@ -258,3 +262,34 @@ def accept_general(logits, draft_tokens, rng_seed, *, n_draft, q_logits=None, q_
         raise ValueError("isd_oracle_accept_general failed: %d" % rc)
     return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, draft_q=dq, row_lse=lse,
                 accept_margin=margin, sample_gap=gap, runner_up=runner, proposal_gap=pgap)
+
+
+def accept_filtered(logits, draft_tokens, rng_seed, *, n_draft, top_k, top_p=1.0, greedy=None, rng_offset=0,
+                    temperature=1.0, tau=0.0, sample_proposals=False):
+    """Acceptance under the filtered sampling distribution (temperature, top-k, top-p) with
+    point-mass proposals (isd_oracle_accept_filtered).  Returns the outputs of `accept` plus
+    kept [B,S] and proposal_gap [B,S]."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, S, V = logits.shape
+    ncol = S - 1
+    dt = None
+    if S > 1:
+        dt = np.ascontiguousarray(np.ascontiguousarray(draft_tokens, dtype=np.int32)[:, :ncol])
+    nd_arr, nd_uni = None, 0
+    if np.isscalar(n_draft):
+        nd_uni = int(n_draft)
+    else:
+        nd_arr = np.ascontiguousarray(n_draft, dtype=np.int32)
+    g = None if greedy is None else np.ascontiguousarray(greedy, dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32); new_tokens = np.zeros((B, S), dtype=np.int32)
+    probs = np.zeros((B, max(ncol, 0))); margin = np.zeros((B, max(ncol, 0)))
+    kept = np.zeros((B, S), dtype=np.int32); gap = np.zeros(B); runner = np.zeros(B, dtype=np.int32); pgap = np.zeros((B, S))
+    rc = lib().isd_oracle_accept_filtered(_ptr(logits), _ptr(dt), int(rng_seed), _ptr(accept_len), _ptr(new_tokens), B, S, V,
+                                          nd_uni, _ptr(nd_arr), _ptr(g), int(rng_offset), float(temperature), float(tau),
+                                          int(top_k), float(top_p), 1 if sample_proposals else 0,
+                                          _ptr(probs) if ncol else None, _ptr(kept), _ptr(margin) if ncol else None,
+                                          _ptr(gap), _ptr(runner), _ptr(pgap))
+    if rc != 0:
+        raise ValueError("isd_oracle_accept_filtered failed: %d" % rc)
+    return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, kept=kept, accept_margin=margin,
+                sample_gap=gap, runner_up=runner, proposal_gap=pgap)

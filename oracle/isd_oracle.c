@@ -517,6 +517,168 @@ int isd_oracle_accept_general(const float* logits, const int32_t* draft_tokens, 
 }
 
 /* ------------------------------------------------------------------------ */
+/* Acceptance under a filtered sampling distribution (top-k, top-p)          */
+/* ------------------------------------------------------------------------ */
+
+typedef struct { double v; int32_t i; } cand_t;
+
+static int cand_cmp(const void* a, const void* b)
+{
+    const cand_t* x = (const cand_t*)a;
+    const cand_t* y = (const cand_t*)b;
+    if (x->v > y->v) return -1;
+    if (x->v < y->v) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+/* The sampling distribution of a row under the set-up the paper's runs use (App. H, ISD
+ * configuration table: temperature 1.0, top_k 50, top_p 0.95), applied in the usual order:
+ * temperature, then the top_k largest logits (equal values: lowest index first), then the
+ * shortest prefix of those, in descending order, whose renormalised probability mass reaches
+ * top_p (at least one element).  Returns the number kept; idx[] their vocabulary ids in
+ * descending order, prob[] their renormalised probabilities. */
+static int filtered_row(const float* l, int V, double T, int top_k, double top_p, cand_t* work,
+                        int32_t* idx, double* prob)
+{
+    for (int i = 0; i < V; ++i) { work[i].v = (double)l[i]; work[i].i = i; }
+    qsort(work, (size_t)V, sizeof(cand_t), cand_cmp);
+    int n = top_k < V ? top_k : V;
+    double sum = 0.0;
+    for (int c = 0; c < n; ++c) { prob[c] = exp((work[c].v - work[0].v) / T); sum += prob[c]; }
+    double cum = 0.0;
+    int keep = n;
+    for (int c = 0; c < n; ++c) {
+        cum += prob[c] / sum;
+        if (cum >= top_p) { keep = c + 1; break; }
+    }
+    double s2 = 0.0;
+    for (int c = 0; c < keep; ++c) s2 += prob[c];
+    for (int c = 0; c < keep; ++c) { prob[c] /= s2; idx[c] = work[c].i; }
+    return keep;
+}
+
+/*
+ * Alg. 1 with point-mass (arg-max or sampled-then-fixed) proposals under the filtered sampling
+ * distribution pf_j of every row (see filtered_row): accept draft x_j iff
+ * u < min(1, (1+tau) pf_j(x_j)) (greedy sequences: x_j == arg-max), resample on the first
+ * rejection from pf_r without x_r, bonus token from pf_D, proposals of the rows after the
+ * drafts: arg-max, or (sample_proposals) a draw from pf_j with random stream 2.  Draws are
+ * Gumbel-max over the kept elements with the noise of their vocabulary ids, so that the
+ * unfiltered case (top_k >= V, top_p = 1) reproduces isd_oracle_accept_general.
+ * Outputs as isd_oracle_accept; kept[b,j] = number of elements of row j that survive the filter.
+ * A rejection when pf_r has no element other than x_r cannot happen for tau = 0 (pf(x) = 1);
+ * should rounding or tau produce it, x_r's row arg-max is emitted.
+ */
+int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                               int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                               int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                               uint32_t rng_offset, double temperature, double tau, int32_t top_k,
+                               double top_p, int32_t sample_proposals, double* draft_probs, int32_t* kept,
+                               double* accept_margin, double* sample_gap, int32_t* runner_up,
+                               double* proposal_gap)
+{
+    if (!logits || !accept_len || !new_tokens) return ORACLE_ERR_ARG;
+    if (B < 0 || S < 1 || V < 1 || !(temperature > 0.0) || !(tau >= 0.0)) return ORACLE_ERR_ARG;
+    if (top_k < 1 || !(top_p > 0.0) || !(top_p <= 1.0)) return ORACLE_ERR_ARG;
+    if (S > 1 && !draft_tokens) return ORACLE_ERR_ARG;
+    const int ncol = S - 1;
+    const int K = top_k < V ? top_k : V;
+    int status = ORACLE_OK;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int D = n_draft ? n_draft[b] : n_draft_uniform;
+        int bad = (D < 0 || D > S - 1);
+        for (int j = 0; !bad && j < D; ++j) {
+            const int x = draft_tokens[(int64_t)b * ncol + j];
+            if (x < 0 || x >= V) bad = 1;
+        }
+        if (bad) {
+#pragma omp critical
+            status = ORACLE_ERR_ARG;
+            continue;
+        }
+        const int is_greedy = greedy ? (greedy[b] != 0) : 0;
+        cand_t* work = (cand_t*)malloc(sizeof(cand_t) * (size_t)V);
+        int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)S * K);
+        double* prob = (double*)malloc(sizeof(double) * (size_t)S * K);
+        int* cnt = (int*)malloc(sizeof(int) * S);
+        for (int j = 0; j < S; ++j) {
+            cnt[j] = filtered_row(logits + ((int64_t)b * S + j) * V, V, temperature, top_k, top_p, work,
+                                  idx + (size_t)j * K, prob + (size_t)j * K);
+            if (kept) kept[(int64_t)b * S + j] = cnt[j];
+        }
+        for (int j = 0; j < ncol; ++j) {
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = 0.0;
+            if (accept_margin) accept_margin[(int64_t)b * ncol + j] = INFINITY;
+        }
+        int r = D, open = 1;
+        for (int j = 0; j < D; ++j) {
+            const int x = draft_tokens[(int64_t)b * ncol + j];
+            double pf = 0.0;
+            for (int c = 0; c < cnt[j]; ++c)
+                if (idx[(size_t)j * K + c] == x) pf = prob[(size_t)j * K + c];
+            if (draft_probs) draft_probs[(int64_t)b * ncol + j] = pf;
+            int ok;
+            if (is_greedy) {
+                ok = (x == idx[(size_t)j * K]);
+            } else {
+                const double u = isd_oracle_accept_uniform(rng_seed, rng_offset, (uint32_t)(b * S + j));
+                double thr = (1.0 + tau) * pf;
+                if (thr > 1.0) thr = 1.0;
+                ok = (u < thr);
+                if (accept_margin) accept_margin[(int64_t)b * ncol + j] = fabs(u - thr);
+            }
+            if (open && !ok) { r = j; open = 0; }
+        }
+        accept_len[b] = r;
+
+        int fresh = idx[(size_t)r * K];
+        double gap = INFINITY;
+        int second = -1;
+        if (!is_greedy) {
+            const int excluded = (r < D) ? draft_tokens[(int64_t)b * ncol + r] : -1;
+            double best = -INFINITY, next = -INFINITY;
+            int found = -1;
+            for (int c = 0; c < cnt[r]; ++c) {
+                const int i = idx[(size_t)r * K + c];
+                if (i == excluded) continue;
+                const double sc = log(prob[(size_t)r * K + c]) + isd_oracle_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + r), (uint32_t)i);
+                if (sc > best || (sc == best && i < found)) { next = best; second = found; best = sc; found = i; }
+                else if (sc > next) { next = sc; second = i; }
+            }
+            if (found >= 0) { fresh = found; gap = best - next; }
+        }
+        if (sample_gap) sample_gap[b] = gap;
+        if (runner_up) runner_up[b] = second;
+
+        for (int j = 0; j < S; ++j) {
+            int32_t tok;
+            double pg = INFINITY;
+            if (j < r) tok = draft_tokens[(int64_t)b * ncol + j];
+            else if (j == r) tok = fresh;
+            else if (j <= D) tok = -1;
+            else if (!sample_proposals || is_greedy) tok = idx[(size_t)j * K];
+            else {
+                double best = -INFINITY, next = -INFINITY;
+                tok = -1;
+                for (int c = 0; c < cnt[j]; ++c) {
+                    const int i = idx[(size_t)j * K + c];
+                    const double sc = log(prob[(size_t)j * K + c]) + proposal_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + j), (uint32_t)i);
+                    if (sc > best || (sc == best && i < tok)) { next = best; best = sc; tok = i; }
+                    else if (sc > next) next = sc;
+                }
+                pg = best - next;
+            }
+            new_tokens[(int64_t)b * S + j] = tok;
+            if (proposal_gap) proposal_gap[(int64_t)b * S + j] = pg;
+        }
+        free(work); free(idx); free(prob); free(cnt);
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Between two steps: KV append, trim-and-commit, next stride                */
 /* ------------------------------------------------------------------------ */
 
