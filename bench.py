@@ -317,6 +317,13 @@ def main():
                "with_sampled_proposals_ms": general(q_logits=q_logits, q_row=q_row, q_lse=q_lse, temperature=0.9,
                                                     tau=0.1, sample_proposals=True)}
         del q_logits, ws_gen
+        ws_f = torch.empty(max(256, idlm.idlm_isd_accept_filtered_workspace(B, S, V)), dtype=torch.uint8, device=dev)
+        gen["filtered_top_k50_top_p095_ms"] = timed(lambda: idlm.idlm_isd_accept_filtered(
+            acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft, greedy=acc.greedy, top_k=50,
+            top_p=0.95, workspace=ws_f), n=5)
+        gen["filtered_with_sampled_proposals_ms"] = timed(lambda: idlm.idlm_isd_accept_filtered(
+            acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft, greedy=acc.greedy, top_k=50,
+            top_p=0.95, sample_proposals=True, workspace=ws_f), n=5)
 
     cpu = None
     if args.cpu_sample > 0 and cfg.dtype == "bf16":

@@ -207,6 +207,37 @@ int idlm_isd_accept_general(const float* logits, const int32_t* draft_tokens, co
 size_t idlm_isd_accept_general_workspace(int32_t B, int32_t S, int32_t V);
 
 /*
+ * idlm_isd_accept_filtered - acceptance under the filtered sampling distribution of the paper's
+ * runs (App. H, ISD configuration table: temperature 1.0, top_k 50, top_p 0.95), with point-mass
+ * proposals (the deployed setting).  The distribution pf_j of row j is built in the usual order:
+ * logits / T, the top_k largest (equal values: lowest index first), then the shortest prefix of
+ * those, in descending order, whose renormalised probability mass reaches top_p (at least one
+ * element), renormalised again.  Then, as in idlm_isd_accept with p replaced by pf:
+ *   accept_j = greedy[b] ? (x_j == argmax) : (u_{b,j} < min(1, (1+tau) pf_j(x_j)))
+ *   fresh token of row r: greedy: arg-max; otherwise a draw from pf_r, without x_r after a
+ *               rejection (the arg-max if nothing else survives the filter)
+ *   proposals of the rows after the drafts: arg-max, or (sample_proposals, non-greedy) a draw
+ *               from pf_j with random stream 2.
+ * A draw is argmax over the surviving ids i of ln pf(i) + Gumbel noise of id i (the noise
+ * idlm_isd_accept uses), so top_k >= V with top_p = 1 reproduces the unfiltered results.
+ *
+ * top_k        1 .. 64.   top_p in (0, 1].   temperature > 0.   tau >= 0.
+ * draft_probs  fp32 [B,S-1] out or NULL: pf_j(x_j) (0 for a draft outside the support).
+ * kept         int32 [B,S] out or NULL: number of ids that survive the filter in each row.
+ * workspace    at least idlm_isd_accept_filtered_workspace(B,S,V) bytes, 256-byte aligned.
+ * One streaming pass over the logits (exact top_k per row), then one small kernel: there is no
+ * second pass.  Same shape limits as idlm_isd_accept.
+ */
+int idlm_isd_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                             int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                             int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                             uint32_t rng_offset, float temperature, float tau, int32_t top_k, float top_p,
+                             int32_t sample_proposals, float* draft_probs, int32_t* kept,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32_t V);
+
+/*
  * idlm_isd_kv_append - batched scatter of the stride's K/V rows into the paged cache, before the
  * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): "KV slots
  * are allocated via a single batched scatter").

@@ -57,7 +57,7 @@ def lib() -> C.CDLL:
         L.isd_oracle_accept_general.restype = C.c_int
         L.isd_oracle_accept_filtered.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
-                                                 C.c_double, C.c_double, C.c_int32, C.c_double, C.c_int32] + [C.c_void_p] * 6
+                                                 C.c_double, C.c_double, C.c_int32, C.c_double, C.c_int32] + [C.c_void_p] * 7
         L.isd_oracle_accept_filtered.restype = C.c_int
         L.isd_oracle_kv_append.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 7 + [C.c_int64] * 3 + [C.c_int32]
         L.isd_oracle_kv_append.restype = C.c_int
@@ -284,12 +284,13 @@ def accept_filtered(logits, draft_tokens, rng_seed, *, n_draft, top_k, top_p=1.0
     accept_len = np.zeros(B, dtype=np.int32); new_tokens = np.zeros((B, S), dtype=np.int32)
     probs = np.zeros((B, max(ncol, 0))); margin = np.zeros((B, max(ncol, 0)))
     kept = np.zeros((B, S), dtype=np.int32); gap = np.zeros(B); runner = np.zeros(B, dtype=np.int32); pgap = np.zeros((B, S))
+    cut = np.zeros((B, S))
     rc = lib().isd_oracle_accept_filtered(_ptr(logits), _ptr(dt), int(rng_seed), _ptr(accept_len), _ptr(new_tokens), B, S, V,
                                           nd_uni, _ptr(nd_arr), _ptr(g), int(rng_offset), float(temperature), float(tau),
                                           int(top_k), float(top_p), 1 if sample_proposals else 0,
                                           _ptr(probs) if ncol else None, _ptr(kept), _ptr(margin) if ncol else None,
-                                          _ptr(gap), _ptr(runner), _ptr(pgap))
+                                          _ptr(gap), _ptr(runner), _ptr(pgap), _ptr(cut))
     if rc != 0:
         raise ValueError("isd_oracle_accept_filtered failed: %d" % rc)
     return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, kept=kept, accept_margin=margin,
-                sample_gap=gap, runner_up=runner, proposal_gap=pgap)
+                sample_gap=gap, runner_up=runner, proposal_gap=pgap, cut_margin=cut)

@@ -538,19 +538,21 @@ static int cand_cmp(const void* a, const void* b)
  * top_p (at least one element).  Returns the number kept; idx[] their vocabulary ids in
  * descending order, prob[] their renormalised probabilities. */
 static int filtered_row(const float* l, int V, double T, int top_k, double top_p, cand_t* work,
-                        int32_t* idx, double* prob)
+                        int32_t* idx, double* prob, double* cut_margin)
 {
     for (int i = 0; i < V; ++i) { work[i].v = (double)l[i]; work[i].i = i; }
     qsort(work, (size_t)V, sizeof(cand_t), cand_cmp);
     int n = top_k < V ? top_k : V;
     double sum = 0.0;
     for (int c = 0; c < n; ++c) { prob[c] = exp((work[c].v - work[0].v) / T); sum += prob[c]; }
-    double cum = 0.0;
+    double cum = 0.0, margin = INFINITY;
     int keep = n;
     for (int c = 0; c < n; ++c) {
         cum += prob[c] / sum;
+        if (c + 1 < n && fabs(cum - top_p) < margin) margin = fabs(cum - top_p);   /* the last prefix is kept anyway */
         if (cum >= top_p) { keep = c + 1; break; }
     }
+    if (cut_margin) *cut_margin = margin;
     double s2 = 0.0;
     for (int c = 0; c < keep; ++c) s2 += prob[c];
     for (int c = 0; c < keep; ++c) { prob[c] /= s2; idx[c] = work[c].i; }
@@ -565,7 +567,9 @@ static int filtered_row(const float* l, int V, double T, int top_k, double top_p
  * drafts: arg-max, or (sample_proposals) a draw from pf_j with random stream 2.  Draws are
  * Gumbel-max over the kept elements with the noise of their vocabulary ids, so that the
  * unfiltered case (top_k >= V, top_p = 1) reproduces isd_oracle_accept_general.
- * Outputs as isd_oracle_accept; kept[b,j] = number of elements of row j that survive the filter.
+ * Outputs as isd_oracle_accept; kept[b,j] = number of elements of row j that survive the filter;
+ * cut_margin[b,j] = distance of the closest cumulative probability from top_p (a single-precision
+ * implementation may cut such a row one element earlier or later when this is tiny).
  * A rejection when pf_r has no element other than x_r cannot happen for tau = 0 (pf(x) = 1);
  * should rounding or tau produce it, x_r's row arg-max is emitted.
  */
@@ -575,7 +579,7 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
                                uint32_t rng_offset, double temperature, double tau, int32_t top_k,
                                double top_p, int32_t sample_proposals, double* draft_probs, int32_t* kept,
                                double* accept_margin, double* sample_gap, int32_t* runner_up,
-                               double* proposal_gap)
+                               double* proposal_gap, double* cut_margin)
 {
     if (!logits || !accept_len || !new_tokens) return ORACLE_ERR_ARG;
     if (B < 0 || S < 1 || V < 1 || !(temperature > 0.0) || !(tau >= 0.0)) return ORACLE_ERR_ARG;
@@ -605,7 +609,8 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
         int* cnt = (int*)malloc(sizeof(int) * S);
         for (int j = 0; j < S; ++j) {
             cnt[j] = filtered_row(logits + ((int64_t)b * S + j) * V, V, temperature, top_k, top_p, work,
-                                  idx + (size_t)j * K, prob + (size_t)j * K);
+                                  idx + (size_t)j * K, prob + (size_t)j * K,
+                                  cut_margin ? cut_margin + (int64_t)b * S + j : NULL);
             if (kept) kept[(int64_t)b * S + j] = cnt[j];
         }
         for (int j = 0; j < ncol; ++j) {

@@ -54,6 +54,11 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_general.restype = C.c_int
         L.idlm_isd_accept_general_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_general_workspace.restype = C.c_size_t
+        L.idlm_isd_accept_filtered.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
+                                               C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, C.c_size_t, vp]
+        L.idlm_isd_accept_filtered.restype = C.c_int
+        L.idlm_isd_accept_filtered_workspace.argtypes = [i32, i32, i32]
+        L.idlm_isd_accept_filtered_workspace.restype = C.c_size_t
         L.idlm_isd_kv_append.argtypes = [vp] * 6 + [i32] * 7 + [i64] * 3 + [i32, vp]
         L.idlm_isd_kv_append.restype = C.c_int
         L.idlm_isd_commit.argtypes = [vp] * 8 + [i32] + [vp] * 5 + [i32] * 6 + [vp]
@@ -256,3 +261,31 @@ def idlm_isd_accept_general(logits, draft_tokens, rng_seed, accept_len, new_toke
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_accept_general")
+
+
+def idlm_isd_accept_filtered_workspace(B, S, V) -> int:
+    return int(lib().idlm_isd_accept_filtered_workspace(B, S, V))
+
+
+def idlm_isd_accept_filtered(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, top_k, top_p=1.0,
+                             greedy=None, rng_offset=0, temperature=1.0, tau=0.0, sample_proposals=False,
+                             draft_probs=None, kept=None, workspace=None, stream=None):
+    """Acceptance under the temperature / top-k / top-p sampling distribution (see idlm.h)."""
+    B, S, V = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    if S > 1:
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, S - 1) and draft_tokens.is_contiguous()
+    nd_uni, nd_arr = (int(n_draft), None) if isinstance(n_draft, int) else (0, n_draft)
+    if nd_arr is not None:
+        assert nd_arr.dtype == torch.int32 and nd_arr.shape == (B,)
+    if draft_probs is not None:
+        assert draft_probs.dtype == torch.float32 and tuple(draft_probs.shape) == (B, S - 1) and draft_probs.is_contiguous()
+    if kept is not None:
+        assert kept.dtype == torch.int32 and tuple(kept.shape) == (B, S) and kept.is_contiguous()
+    rc = lib().idlm_isd_accept_filtered(
+        _ptr(logits), _ptr(draft_tokens) if S > 1 else None, int(rng_seed), _ptr(accept_len), _ptr(new_tokens), B, S, V,
+        nd_uni, _ptr(nd_arr), _ptr(greedy), int(rng_offset), float(temperature), float(tau), int(top_k), float(top_p),
+        1 if sample_proposals else 0, _ptr(draft_probs), _ptr(kept), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_accept_filtered")

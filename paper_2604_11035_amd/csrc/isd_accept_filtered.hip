@@ -1,0 +1,321 @@
+// Acceptance under the filtered sampling distribution of the paper's runs (App. H, ISD
+// configuration table: temperature, top_k 50, top_p 0.95) with point-mass proposals:
+//   1. one streaming pass per logit row that keeps the exact top_k (<= 64) elements, in
+//      descending order, equal values by ascending index;
+//   2. per sequence (one wavefront, lane = candidate): temperature, top-p cut, renormalisation,
+//      accept tests, and every draw (fresh token, sampled proposals) as a Gumbel-max over the
+//      at most 64 surviving candidates - no second pass over the logits.
+// HBM-bound: one read of the logits.
+#include "isd_accept_common.h"
+
+namespace idlm {
+
+constexpr int kTopKMax = 64;       // candidates per row (one per lane of the second kernel)
+constexpr int kBufCap = 2048;      // candidate buffer of the streaming pass (keys in LDS)
+
+// (value, index) as one 64-bit key whose unsigned order is "larger value first, then lower index".
+__device__ __forceinline__ unsigned long long cand_key(float v, int idx)
+{
+    const uint32_t bits = __float_as_uint(v);
+    const uint32_t ordered = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return ((unsigned long long)ordered << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)idx);
+}
+__device__ __forceinline__ float key_value(unsigned long long key)
+{
+    const uint32_t o = (uint32_t)(key >> 32);
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+__device__ __forceinline__ int key_index(unsigned long long key) { return (int)(0xFFFFFFFFu - (uint32_t)key); }
+
+// Sorts buf[0..n) in descending order (bitonic network, 256 threads); n is a power of two that
+// covers the entries in use, the others are 0.  All threads of the block call it.
+__device__ void sort_buffer_desc(unsigned long long* buf, int n)
+{
+    const int tid = threadIdx.x;
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < n / 2; t += 256) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));   // lower partner: bit j clear
+                const int l = i | j;
+                const bool desc = (i & k) == 0;
+                const unsigned long long a = buf[i], b = buf[l];
+                if ((a < b) == desc) { buf[i] = b; buf[l] = a; }
+            }
+            __syncthreads();
+        }
+}
+
+// One workgroup per row.  Elements above the current threshold (the K-th largest key seen so
+// far, 0 before K elements have been seen) are appended to a buffer; when the buffer cannot take
+// the next batch it is sorted and cut back to its K largest, which raises the threshold.  On
+// unordered data only a few hundred elements of a 150k row ever pass, so the pass streams.
+template <int UNROLL>
+__global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restrict__ logits, int V, int K,
+                                                           unsigned long long* __restrict__ out_keys)
+{
+    __shared__ unsigned long long buf[kBufCap];
+    __shared__ int s_count, s_want;
+    __shared__ unsigned long long s_thr;
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const f32x4* __restrict__ p4 = reinterpret_cast<const f32x4*>(logits + (size_t)row * V);
+    const int fend = V >> 2;
+    for (int t = tid; t < kBufCap; t += 256) buf[t] = 0ull;
+    if (tid == 0) { s_count = 0; s_thr = 0ull; }
+    __syncthreads();
+
+    auto prune = [&]() {           // every thread; buffer -> its K largest, threshold raised
+        const int used = s_count;
+        int n2 = 64;
+        while (n2 < used) n2 <<= 1;
+        sort_buffer_desc(buf, n2);
+        const int kept = min(used, K);
+        for (int t = kept + tid; t < n2; t += 256) buf[t] = 0ull;
+        if (tid == 0) {
+            s_count = kept;
+            s_thr = kept == K ? buf[K - 1] : 0ull;
+        }
+        __syncthreads();
+    };
+
+    for (int base = 0; base < fend; base += UNROLL * 256) {
+        f32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int f = base + u * 256 + tid;
+            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        }
+        const unsigned long long thr = s_thr;
+        const float thr_v = thr ? key_value(thr) : -INFINITY;
+        // candidates by value alone (elements beyond the row read as -inf and never pass once a
+        // threshold exists; before that the exact test below drops them); the exact (value, index)
+        // test is only paid by the few that get this far
+        int mine = 0;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine += (v[u][e] >= thr_v) ? 1 : 0;
+        if (tid == 0) s_want = 0;
+        if (!__syncthreads_or(mine)) continue;       // nothing in this batch reaches the threshold
+        if (mine) atomicAdd(&s_want, mine);
+        __syncthreads();
+        if (s_count + s_want <= kBufCap) {
+            // the common case: everything that passes fits
+            if (mine) {
+                int exact = 0;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int f = base + u * 256 + tid;
+                    if (f < fend)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            exact += (v[u][e] >= thr_v && cand_key(v[u][e], f * 4 + e) > thr) ? 1 : 0;
+                }
+                int slot = exact ? atomicAdd(&s_count, exact) : 0;
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int f = base + u * 256 + tid;
+                    if (f < fend)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned long long key = cand_key(v[u][e], f * 4 + e);
+                            if (v[u][e] >= thr_v && key > thr) buf[slot++] = key;
+                        }
+                }
+            }
+            __syncthreads();
+        } else {
+            // too many for the buffer (the first batch of a row, or adversarially ordered data): 1024
+            // elements at a time, cutting the buffer back as soon as it holds 1024 keys
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                if (s_count >= 1024) prune();
+                else __syncthreads();
+                const unsigned long long t2 = s_thr;
+                const int f = base + u * 256 + tid;
+                if (f < fend) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const unsigned long long key = cand_key(v[u][e], f * 4 + e);
+                        if (key > t2) buf[atomicAdd(&s_count, 1)] = key;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    prune();
+    if (tid < kTopKMax) out_keys[(size_t)row * kTopKMax + tid] = tid < s_count ? buf[tid] : 0ull;
+}
+
+struct FilteredParams {
+    const int32_t* draft_tokens;
+    const unsigned long long* cand;     // [rows][64] keys in descending order, 0 = none
+    int32_t* accept_len;
+    int32_t* new_tokens;
+    const int32_t* n_draft;
+    const uint8_t* greedy;
+    float* draft_probs;
+    int32_t* kept;
+    uint2 key;
+    int S, V, n_draft_uniform, sample_proposals;
+    uint32_t rng_offset;
+    float k;              // log2(e) / T
+    float one_plus_tau;
+    float top_p;
+};
+
+// The filtered distribution of one row over the wavefront's lanes: lane c holds candidate c.
+// Returns the number of candidates kept; pf = renormalised probability (0 for lanes not kept).
+__device__ __forceinline__ int filtered_row(const FilteredParams& p, int row, int lane, int& idx, float& pf)
+{
+    const unsigned long long key = p.cand[(size_t)row * kTopKMax + lane];
+    const int n = __builtin_popcountll(__ballot(key != 0ull));
+    idx = key ? key_index(key) : -1;
+    const float val = key ? key_value(key) : -INFINITY;
+    const float top = __shfl(val, 0);
+    const float w = key ? fast_exp2((val - top) * p.k) : 0.f;
+    float cum = w;                          // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float y = __shfl_up(cum, off);
+        if (lane >= off) cum += y;
+    }
+    const float total = __shfl(cum, 63);
+    const unsigned long long reached = __ballot(lane < n && cum >= p.top_p * total);
+    const int keep = reached ? min(n, (int)__builtin_ctzll(reached) + 1) : n;
+    const float s2 = __shfl(cum, keep - 1);
+    pf = lane < keep ? w / s2 : 0.f;
+    return keep;
+}
+
+// Gumbel-max draw among the kept candidates of a row (noise of the candidates' vocabulary ids);
+// `excluded` is left out; returns -1 if nothing qualifies.
+__device__ __forceinline__ int draw(const FilteredParams& p, int row, int stream, int idx, float pf, int excluded)
+{
+    float score = -INFINITY;
+    if (pf > 0.f && idx != excluded) {
+        const uint4 w = philox4x32_10(make_uint4((uint32_t)idx >> 2, (uint32_t)row, (uint32_t)stream, p.rng_offset), p.key);
+        const uint32_t word = (idx & 3) == 0 ? w.x : (idx & 3) == 1 ? w.y : (idx & 3) == 2 ? w.z : w.w;
+        score = logf(pf) + gumbel(word);
+    }
+    int best = score > -INFINITY ? idx : INT_MAX;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float s2 = __shfl_xor(score, off);
+        const int i2 = __shfl_xor(best, off);
+        combine_best(score, best, s2, i2);
+    }
+    return best == INT_MAX ? -1 : best;
+}
+
+__global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const FilteredParams p)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int S = p.S, ncol = S - 1;
+    const bool is_greedy = p.greedy ? (p.greedy[b] != 0) : false;
+    int D = p.n_draft ? p.n_draft[b] : p.n_draft_uniform;
+    D = max(0, min(D, S - 1));
+
+    // accept tests of the drafts, in order; r = first failure
+    int r = D;
+    for (int j = 0; j < S; ++j) {
+        const int row = b * S + j;
+        int idx;
+        float pf;
+        const int keep = filtered_row(p, row, lane, idx, pf);
+        if (p.kept && lane == 0) p.kept[row] = keep;
+        if (j < ncol) {
+            float px = 0.f;
+            bool ok = true;
+            if (j < D) {
+                const int x = p.draft_tokens[(size_t)b * ncol + j];
+                const unsigned long long hit = __ballot(idx == x && pf > 0.f);
+                px = hit ? __shfl(pf, (int)__builtin_ctzll(hit)) : 0.f;
+                if (is_greedy) {
+                    ok = (x == __shfl(idx, 0));
+                } else {
+                    const uint4 w = philox4x32_10(make_uint4(0u, (uint32_t)row, 0u, p.rng_offset), p.key);
+                    ok = unit_uniform(w.x) < fminf(1.f, p.one_plus_tau * px);
+                }
+                if (!ok && j < r) r = j;
+            }
+            if (p.draft_probs && lane == 0) p.draft_probs[(size_t)b * ncol + j] = px;
+        }
+    }
+    if (lane == 0) p.accept_len[b] = r;
+
+    // tokens
+    for (int j = 0; j < S; ++j) {
+        const int row = b * S + j;
+        int tok;
+        if (j < r) tok = p.draft_tokens[(size_t)b * ncol + j];
+        else if (j > r && j <= D) tok = -1;
+        else {
+            int idx;
+            float pf;
+            filtered_row(p, row, lane, idx, pf);
+            const int top = __shfl(idx, 0);
+            tok = top;
+            if (!is_greedy) {
+                if (j == r) {
+                    const int excluded = (r < D) ? p.draft_tokens[(size_t)b * ncol + r] : -1;
+                    const int got = draw(p, row, 1, idx, pf, excluded);
+                    if (got >= 0) tok = got;
+                } else if (p.sample_proposals) {
+                    const int got = draw(p, row, 2, idx, pf, -1);
+                    if (got >= 0) tok = got;
+                }
+            }
+        }
+        if (lane == 0) p.new_tokens[row] = tok;
+    }
+}
+
+}  // namespace idlm
+
+using namespace idlm;
+
+extern "C" size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32_t V)
+{
+    if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return 0;
+    if (B == 0) return 0;
+    return align256((size_t)B * S * kTopKMax * sizeof(unsigned long long));
+}
+
+extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                        int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                                        int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                                        uint32_t rng_offset, float temperature, float tau, int32_t top_k, float top_p,
+                                        int32_t sample_proposals, float* draft_probs, int32_t* kept,
+                                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
+    if (!n_draft && (n_draft_uniform < 0 || n_draft_uniform > S - 1)) return IDLM_ERR_SHAPE;
+    if (!(temperature > 0.f) || !(tau >= 0.f) || !(temperature < INFINITY) || !(tau < INFINITY)) return IDLM_ERR_SHAPE;
+    if (top_k < 1 || top_k > kTopKMax || !(top_p > 0.f) || !(top_p <= 1.f)) return IDLM_ERR_SHAPE;
+    if (B == 0) return IDLM_OK;
+    if (!logits || !accept_len || !new_tokens) return IDLM_ERR_NULL;
+    if (S > 1 && !draft_tokens) return IDLM_ERR_NULL;
+    if (!aligned(logits, 16)) return IDLM_ERR_ALIGN;
+    const size_t need = idlm_isd_accept_filtered_workspace(B, S, V);
+    if (!workspace || workspace_bytes < need) return IDLM_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return IDLM_ERR_ALIGN;
+
+    FilteredParams p;
+    p.draft_tokens = draft_tokens;
+    p.cand = static_cast<unsigned long long*>(workspace);
+    p.accept_len = accept_len; p.new_tokens = new_tokens; p.n_draft = n_draft; p.greedy = greedy;
+    p.draft_probs = draft_probs; p.kept = kept;
+    p.key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
+    p.S = S; p.V = V; p.n_draft_uniform = n_draft_uniform; p.sample_proposals = sample_proposals ? 1 : 0;
+    p.rng_offset = rng_offset;
+    p.k = kLog2e / temperature;
+    p.one_plus_tau = 1.f + tau;
+    p.top_p = top_p;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(isd_row_topk_kernel<16>, dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
+                       top_k < V ? top_k : V, static_cast<unsigned long long*>(workspace));
+    hipLaunchKernelGGL(isd_accept_filtered_chain_kernel, dim3((unsigned)B), dim3(64), 0, st, p);
+    return launch_status();
+}

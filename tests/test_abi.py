@@ -189,3 +189,30 @@ def test_general_accept_workspace_and_empty_batch():
     g = idlm.idlm_isd_accept_general_workspace(256, 16, 151936)
     assert g > idlm.idlm_isd_accept_workspace(256, 16, 151936) and g % 256 == 0
     assert idlm.idlm_isd_accept_general_workspace(4, 4, 1023) == 0
+
+
+def _filtered(**kw):
+    a = dict(logits=FAKE, drafts=FAKE, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024, ndu=1, nd=None, greedy=None, off=0,
+             T=1.0, tau=0.0, top_k=50, top_p=0.95, samp=0, probs=None, kept=None, ws=None, ws_bytes=0, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_isd_accept_filtered(a["logits"], a["drafts"], a["seed"], a["alen"], a["toks"], a["B"], a["S"],
+                                               a["V"], a["ndu"], a["nd"], a["greedy"], a["off"], a["T"], a["tau"],
+                                               a["top_k"], a["top_p"], a["samp"], a["probs"], a["kept"], a["ws"],
+                                               a["ws_bytes"], a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(logits=None), -1), (dict(alen=None), -1), (dict(drafts=None), -1),
+    (dict(S=65), -2), (dict(V=6), -2), (dict(top_k=0), -2), (dict(top_k=65), -2), (dict(top_p=0.0), -2), (dict(top_p=1.5), -2),
+    (dict(T=0.0), -2), (dict(tau=-1.0), -2),
+    (dict(logits=ODD), -4),
+    (dict(), -5), (dict(ws=FAKE, ws_bytes=128), -5),
+])
+def test_filtered_accept_rejects_bad_arguments(kw, code):
+    assert _filtered(**kw) == code
+
+
+def test_filtered_accept_workspace_and_empty_batch():
+    assert _filtered(B=0) == 0
+    assert idlm.idlm_isd_accept_filtered_workspace(256, 16, 151936) == 256 * 16 * 64 * 8
+    assert idlm.idlm_isd_accept_filtered_workspace(4, 4, 1023) == 0
