@@ -155,3 +155,21 @@ def test_repeatable_and_empty_batch():
     idlm.idlm_isd_attention(q, inp.k_cache, inp.v_cache, torch.empty(0, 4, dtype=torch.int32, device=DEV),
                             torch.empty(0, dtype=torch.int32, device=DEV), 4, torch.empty_like(q))
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_grids_and_layouts(case):
+    """Seeded random draws over batch size, stride, head grouping (also group sizes that are not
+    powers of two), context lengths around tile and page boundaries, grid sizes and pool layout."""
+    rng = np.random.default_rng(1000 + case)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    S = int(rng.integers(1, min(32, 256 // G) + 1))
+    B = int(rng.integers(1, 24))
+    hi = int(rng.choice([40, 200, 700]))
+    ctx = [int(c) for c in rng.integers(S, S + hi, size=B)]
+    for k in range(min(3, B)):                       # a few lengths right at tile / page edges
+        ctx[k] = max(S, int(rng.choice([16, 17, 31, 32, 33, 63, 64, 65, 96, 128, 129])))
+    inp = _manual(B, S, Hkv * G, Hkv, ctx, seed=5000 + case, token_major=bool(rng.integers(0, 2)))
+    for nwg in (0, int(rng.choice([1, 2, 3, 7, 17, 64, 300, 1024]))):
+        _check(inp, num_workgroups=nwg)
