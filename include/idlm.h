@@ -168,6 +168,31 @@ int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
 
 /*
+ * idlm_isd_accept_bf16 - the same acceptance (Alg. 1, introspection loop; Sec. 3.3 (3)) over
+ * logits stored as bf16, which halves the bytes the pass has to read.  Every logit widens
+ * exactly to fp32 and all arithmetic after the load is that of idlm_isd_accept, so the results
+ * are those of idlm_isd_accept called on the widened values: same rules, same random streams,
+ * same tie rule (bf16 rows hold many equal values; arg-max ties go to the lowest index).
+ *
+ * logits  bf16 (raw 16-bit patterns) [B,S,V] contiguous, 16-byte aligned; V % 8 == 0, V >= 8.
+ * All other arguments, the workspace size (idlm_isd_accept_workspace) and the error behaviour
+ * are those of idlm_isd_accept; the _ev form records the same three events.
+ */
+int idlm_isd_accept_bf16(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                         int32_t* accept_len, int32_t* new_tokens,
+                         int32_t B, int32_t S, int32_t V,
+                         int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                         uint32_t rng_offset, float* draft_probs,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+int idlm_isd_accept_bf16_ev(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                            int32_t* accept_len, int32_t* new_tokens,
+                            int32_t B, int32_t S, int32_t V,
+                            int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                            uint32_t rng_offset, float* draft_probs,
+                            void* workspace, size_t workspace_bytes, void* stream, void* const* events);
+
+/*
  * idlm_isd_accept_general - acceptance with general proposal distributions, sampling
  * temperature, relaxed threshold and sampled proposals: Alg. 1 as printed (drafts drawn from
  * q_j, accepted with probability min(1, p_j(x_j)/q_j(x_j)), resampled from

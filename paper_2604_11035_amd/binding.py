@@ -47,6 +47,10 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept.restype = C.c_int
         L.idlm_isd_accept_ev.argtypes = L.idlm_isd_accept.argtypes + [vp]
         L.idlm_isd_accept_ev.restype = C.c_int
+        L.idlm_isd_accept_bf16.argtypes = L.idlm_isd_accept.argtypes
+        L.idlm_isd_accept_bf16.restype = C.c_int
+        L.idlm_isd_accept_bf16_ev.argtypes = L.idlm_isd_accept_ev.argtypes
+        L.idlm_isd_accept_bf16_ev.restype = C.c_int
         L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_workspace.restype = C.c_size_t
         L.idlm_isd_accept_general.argtypes = [vp, vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp,
@@ -147,13 +151,27 @@ def idlm_isd_accept_workspace(B, S, V) -> int:
 
 def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
                     rng_offset=0, draft_probs=None, workspace=None, stream=None, events=None):
-    """Introspective acceptance over logits [B,S,V] (see idlm.h).
+    """Introspective acceptance over fp32 logits [B,S,V] (see idlm.h).
 
     n_draft: int (uniform) or int32 device tensor [B]; greedy: uint8 device tensor [B] or None.
     accept_len int32 [B] and new_tokens int32 [B,S] are written; draft_probs fp32 [B,S-1] optional.
     """
+    return _accept(lib().idlm_isd_accept_ev, "idlm_isd_accept", torch.float32, logits, draft_tokens, rng_seed,
+                   accept_len, new_tokens, n_draft, greedy, rng_offset, draft_probs, workspace, stream, events)
+
+
+def idlm_isd_accept_bf16(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
+                         rng_offset=0, draft_probs=None, workspace=None, stream=None, events=None):
+    """The same acceptance over bf16 logits [B,S,V] (half the bytes per row; see idlm.h)."""
+    return _accept(lib().idlm_isd_accept_bf16_ev, "idlm_isd_accept_bf16", torch.bfloat16, logits, draft_tokens,
+                   rng_seed, accept_len, new_tokens, n_draft, greedy, rng_offset, draft_probs, workspace, stream,
+                   events)
+
+
+def _accept(fn, name, dtype, logits, draft_tokens, rng_seed, accept_len, new_tokens, n_draft, greedy,
+            rng_offset, draft_probs, workspace, stream, events):
     B, S, V = logits.shape
-    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    assert logits.dtype == dtype and logits.is_contiguous()
     assert accept_len.dtype == torch.int32 and new_tokens.dtype == torch.int32
     assert accept_len.numel() == B and new_tokens.shape == (B, S) and new_tokens.is_contiguous()
     if draft_tokens is not None:
@@ -170,13 +188,13 @@ def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n
     if draft_probs is not None:
         assert draft_probs.dtype == torch.float32 and draft_probs.is_contiguous()
         assert draft_probs.numel() == B * (S - 1)
-    rc = lib().idlm_isd_accept_ev(
+    rc = fn(
         _ptr(logits), _ptr(draft_tokens), int(rng_seed), _ptr(accept_len), _ptr(new_tokens),
         B, S, V, nd_uni, nd_ptr, _ptr(greedy), int(rng_offset), _ptr(draft_probs),
         _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream), _events_arg(events))
     if rc != 0:
-        raise IdlmError(rc, "idlm_isd_accept")
+        raise IdlmError(rc, name)
     return accept_len, new_tokens
 
 

@@ -33,8 +33,9 @@ struct ChainResult {   // what the sampling pass needs to know about a sequence
     int excluded;      // token id removed from the sample (the rejected draft), or -1
 };
 
+template <bool BF16>
 __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
-    const float* __restrict__ logits, const int32_t* __restrict__ draft_tokens, uint2 key,
+    const void* __restrict__ logits, const int32_t* __restrict__ draft_tokens, uint2 key,
     int32_t* __restrict__ accept_len, int32_t* __restrict__ new_tokens, int S, int V,
     int n_draft_uniform, const int32_t* __restrict__ n_draft, const uint8_t* __restrict__ greedy,
     uint32_t rng_offset, float* __restrict__ draft_probs, const RowPartial* __restrict__ stats,
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
         if (tid < n_d) {
             x = draft_tokens[(size_t)b * ncol + tid];
             if (x >= 0 && x < V) {
-                const float lx = logits[(size_t)row * V + x];
+                const float lx = LogitVec<BF16>::element(logits, (size_t)row * V + x);
                 p = fast_exp2(fmaf(lx, kLog2e, -ref_log2(m))) / z;
             }
             if (is_greedy) {
@@ -95,10 +96,14 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
 
 // ---- pass 3: Gumbel-max sample of the one row per stochastic sequence -------------------------
 
+template <bool BF16>
 __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
-    const float* __restrict__ logits, uint2 key, int S, int V, uint32_t rng_offset,
+    const void* __restrict__ logits, uint2 key, int S, int V, uint32_t rng_offset,
     const ChainResult* __restrict__ chain, unsigned long long* keys, int nsb, int gchunk)
 {
+    typedef LogitVec<BF16> LV;
+    typedef typename LV::raw raw_t;
+    constexpr int N = LV::N;
     const int b = blockIdx.x / nsb;
     const int c = blockIdx.x - b * nsb;
     const int tid = threadIdx.x;
@@ -111,21 +116,26 @@ __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
     // Gumbel-max over slice c of row r: argmax_i (l_i + g_i), the rejected draft excluded
     const int excluded = cr.excluded;
     const uint32_t row = (uint32_t)(b * S + cr.row);
-    const float4* __restrict__ p4 = reinterpret_cast<const float4*>(logits + (size_t)row * V);
-    const int fbeg = (c * gchunk) >> 2;
-    const int fend = min(V, (c + 1) * gchunk) >> 2;
+    const raw_t* __restrict__ pv = reinterpret_cast<const raw_t*>(
+        static_cast<const char*>(logits) + (size_t)row * V * (16 / N));
+    const int fbeg = (c * gchunk) / N;
+    const int fend = min(V, (c + 1) * gchunk) / N;
     float best = -INFINITY;
     int bidx = INT_MAX;
     for (int f = fbeg + tid; f < fend; f += 256) {
-        const float4 v = p4[f];
-        const uint4 w = philox4x32_10(make_uint4((uint32_t)f, row, 1u, rng_offset), key);
-        const float s0 = v.x + gumbel(w.x), s1 = v.y + gumbel(w.y);
-        const float s2 = v.z + gumbel(w.z), s3 = v.w + gumbel(w.w);
-        const int i0 = f * 4;
-        if (i0 != excluded && s0 > best) { best = s0; bidx = i0; }
-        if (i0 + 1 != excluded && s1 > best) { best = s1; bidx = i0 + 1; }
-        if (i0 + 2 != excluded && s2 > best) { best = s2; bidx = i0 + 2; }
-        if (i0 + 3 != excluded && s3 > best) { best = s3; bidx = i0 + 3; }
+        float e[N];
+        LV::unpack(pv[f], e);
+#pragma unroll
+        for (int h = 0; h < N / 4; ++h) {   // one Philox block per four consecutive elements
+            const int i0 = f * N + h * 4;
+            const uint4 w = philox4x32_10(make_uint4((uint32_t)(i0 >> 2), row, 1u, rng_offset), key);
+            const float s0 = e[h * 4] + gumbel(w.x), s1 = e[h * 4 + 1] + gumbel(w.y);
+            const float s2 = e[h * 4 + 2] + gumbel(w.z), s3 = e[h * 4 + 3] + gumbel(w.w);
+            if (i0 != excluded && s0 > best) { best = s0; bidx = i0; }
+            if (i0 + 1 != excluded && s1 > best) { best = s1; bidx = i0 + 1; }
+            if (i0 + 2 != excluded && s2 > best) { best = s2; bidx = i0 + 2; }
+            if (i0 + 3 != excluded && s3 > best) { best = s3; bidx = i0 + 3; }
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -167,14 +177,17 @@ extern "C" size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V)
     return layout(B, S, make_plan(B, S, V)).total;
 }
 
-extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                                  int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
-                                  int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
-                                  const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
-                                  void* workspace, size_t workspace_bytes, void* stream,
-                                  void* const* events)
+namespace idlm {
+
+template <bool BF16>
+static int accept_impl(const void* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                       int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                       int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                       uint32_t rng_offset, float* draft_probs, void* workspace, size_t workspace_bytes,
+                       void* stream, void* const* events)
 {
-    if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
+    constexpr int N = LogitVec<BF16>::N;   // elements per 16-byte vector
+    if (B < 0 || S < 1 || S > 64 || V < N || (V % N) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
     if (!n_draft && (n_draft_uniform < 0 || n_draft_uniform > S - 1)) return IDLM_ERR_SHAPE;
     if (B == 0) return IDLM_OK;
     if (!logits || !accept_len || !new_tokens) return IDLM_ERR_NULL;
@@ -193,20 +206,34 @@ extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_toke
 
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
-    hipLaunchKernelGGL(isd_row_stats_kernel<16>, dim3((unsigned)(B * S * plan.nsplit)), dim3(256), 0, st,
+    hipLaunchKernelGGL((isd_row_stats_kernel<16, BF16>), dim3((unsigned)(B * S * plan.nsplit)), dim3(256), 0, st,
                        logits, V, plan.chunk, plan.nsplit, S, stats, kLog2e);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const uint2 key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
     ChainResult* chain = reinterpret_cast<ChainResult*>(ws + w.chain_off);
-    hipLaunchKernelGGL(isd_accept_chain_kernel, dim3((unsigned)B), dim3(64), 0, st, logits, draft_tokens, key,
-                       accept_len, new_tokens, S, V, n_draft_uniform, n_draft, greedy, rng_offset, draft_probs,
-                       stats, plan.nsplit, chain, keys);
-    hipLaunchKernelGGL(isd_accept_sample_kernel, dim3((unsigned)(B * plan.nsb)), dim3(256), 0, st, logits, key,
-                       S, V, rng_offset, chain, keys, plan.nsb, plan.gchunk);
+    hipLaunchKernelGGL(isd_accept_chain_kernel<BF16>, dim3((unsigned)B), dim3(64), 0, st, logits, draft_tokens,
+                       key, accept_len, new_tokens, S, V, n_draft_uniform, n_draft, greedy, rng_offset,
+                       draft_probs, stats, plan.nsplit, chain, keys);
+    hipLaunchKernelGGL(isd_accept_sample_kernel<BF16>, dim3((unsigned)(B * plan.nsb)), dim3(256), 0, st, logits,
+                       key, S, V, rng_offset, chain, keys, plan.nsb, plan.gchunk);
     hipLaunchKernelGGL(isd_accept_emit_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, st, chain, keys,
                        new_tokens, B, S);
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
+}
+
+}  // namespace idlm
+
+extern "C" int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                  int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                                  int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                  const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  void* const* events)
+{
+    return accept_impl<false>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
+                              n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
+                              workspace_bytes, stream, events);
 }
 
 extern "C" int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
@@ -215,7 +242,30 @@ extern "C" int idlm_isd_accept(const float* logits, const int32_t* draft_tokens,
                                const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
                                void* workspace, size_t workspace_bytes, void* stream)
 {
-    return idlm_isd_accept_ev(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
+    return accept_impl<false>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
                               n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
                               workspace_bytes, stream, nullptr);
+}
+
+extern "C" int idlm_isd_accept_bf16_ev(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                       int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                                       int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                       const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       void* const* events)
+{
+    return accept_impl<true>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
+                             n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
+                             workspace_bytes, stream, events);
+}
+
+extern "C" int idlm_isd_accept_bf16(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                    int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                                    int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                    const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return accept_impl<true>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
+                             n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
+                             workspace_bytes, stream, nullptr);
 }

@@ -54,69 +54,118 @@ __device__ __forceinline__ void combine_best(float& s, int& i, float s2, int i2)
     if (s2 > s || (s2 == s && i2 < i)) { s = s2; i = i2; }
 }
 
+// ---- logit rows in fp32 or bf16 --------------------------------------------------------------
+// A row is streamed in 16-byte vectors: 4 fp32 values, or 8 bf16 values that widen to fp32 exactly
+// (a bf16 is the upper half of the fp32 with the same value).
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+template <bool BF16> struct LogitVec;
+
+template <> struct LogitVec<false> {
+    static constexpr int N = 4;
+    typedef f32x4 raw;
+    __device__ static __forceinline__ void unpack(const raw& r, float (&v)[4])
+    {
+        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+    }
+    __device__ static __forceinline__ float element(const void* base, size_t i)
+    {
+        return static_cast<const float*>(base)[i];
+    }
+};
+
+template <> struct LogitVec<true> {
+    static constexpr int N = 8;
+    typedef u32x4 raw;
+    __device__ static __forceinline__ void unpack(const raw& r, float (&v)[8])
+    {
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    }
+    __device__ static __forceinline__ float element(const void* base, size_t i)
+    {
+        return __uint_as_float((uint32_t)static_cast<const uint16_t*>(base)[i] << 16);
+    }
+};
+
 // ---- pass 1: row statistics ---------------------------------------------------------------
 
-template <int UNROLL>
-__global__ __launch_bounds__(256) void isd_row_stats_kernel(const float* __restrict__ logits, int V,
+template <int UNROLL, bool BF16 = false>
+__global__ __launch_bounds__(256) void isd_row_stats_kernel(const void* __restrict__ logits, int V,
                                                             int chunk, int nsplit, int S,
                                                             RowPartial* __restrict__ stats, float k)
 {
+    typedef LogitVec<BF16> LV;
+    typedef typename LV::raw raw_t;
+    constexpr int N = LV::N;
     const int row = blockIdx.x / nsplit;
     const int c = blockIdx.x - row * nsplit;
     const int tid = threadIdx.x;
-    const f32x4* __restrict__ p4 = reinterpret_cast<const f32x4*>(logits + (size_t)row * V);
-    const int fbeg = (c * chunk) >> 2;
-    const int fend = min(V, (c + 1) * chunk) >> 2;
-
+    const raw_t* __restrict__ pv = reinterpret_cast<const raw_t*>(
+        static_cast<const char*>(logits) + (size_t)row * V * (16 / N));
+    const int fbeg = (c * chunk) / N;
+    const int fend = min(V, (c + 1) * chunk) / N;
 
     float m = -INFINITY;   // running maximum of this thread's elements
-    float z = 0.f;         // sum of 2^(l*log2e - ref_log2(m))
-    int arg4 = -1;         // float4 index that holds the first occurrence of m
+    float z = 0.f;         // sum of 2^(l*k - ref_k(m, k))
+    int argv = -1;         // index of the vector that holds the first occurrence of m
 
     int f = fbeg + tid;
     for (; f + (UNROLL - 1) * 256 < fend; f += UNROLL * 256) {
-        f32x4 v[UNROLL];
+        raw_t v[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(p4 + f + u * 256);
+        for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(pv + f + u * 256);
         float newm = m;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            const float bm = fmaxf(fmaxf(v[u].x, v[u].y), fmaxf(v[u].z, v[u].w));
-            if (bm > newm) { newm = bm; arg4 = f + u * 256; }
+            float e[N];
+            LV::unpack(v[u], e);
+            float bm = e[0];
+#pragma unroll
+            for (int i = 1; i < N; ++i) bm = fmaxf(bm, e[i]);
+            if (bm > newm) { newm = bm; argv = f + u * 256; }
         }
         const float r = ref_k(newm, k);
         float acc = z * rescale_k(m, r, k);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            acc += fast_exp2(fmaf(v[u].x, k, -r));
-            acc += fast_exp2(fmaf(v[u].y, k, -r));
-            acc += fast_exp2(fmaf(v[u].z, k, -r));
-            acc += fast_exp2(fmaf(v[u].w, k, -r));
+            float e[N];
+            LV::unpack(v[u], e);
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc += fast_exp2(fmaf(e[i], k, -r));
         }
         z = acc;
         m = newm;
     }
     for (; f < fend; f += 256) {
-        const f32x4 v = __builtin_nontemporal_load(p4 + f);
-        const float bm = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+        const raw_t v = __builtin_nontemporal_load(pv + f);
+        float e[N];
+        LV::unpack(v, e);
+        float bm = e[0];
+#pragma unroll
+        for (int i = 1; i < N; ++i) bm = fmaxf(bm, e[i]);
         float newm = m;
-        if (bm > newm) { newm = bm; arg4 = f; }
+        if (bm > newm) { newm = bm; argv = f; }
         const float r = ref_k(newm, k);
         float acc = z * rescale_k(m, r, k);
-        acc += fast_exp2(fmaf(v.x, k, -r));
-        acc += fast_exp2(fmaf(v.y, k, -r));
-        acc += fast_exp2(fmaf(v.z, k, -r));
-        acc += fast_exp2(fmaf(v.w, k, -r));
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc += fast_exp2(fmaf(e[i], k, -r));
         z = acc;
         m = newm;
     }
 
-    // which of the four components was first to reach m
+    // which component of that vector was first to reach m
     int arg = INT_MAX;
-    if (arg4 >= 0) {
-        const f32x4 v = p4[arg4];
-        const int lane = (v.x == m) ? 0 : (v.y == m) ? 1 : (v.z == m) ? 2 : 3;
-        arg = arg4 * 4 + lane;
+    if (argv >= 0) {
+        float e[N];
+        LV::unpack(pv[argv], e);
+        int lane = N - 1;
+#pragma unroll
+        for (int i = N - 2; i >= 0; --i) lane = (e[i] == m) ? i : lane;
+        arg = argv * N + lane;
     }
 
     // wavefront reduction, then the four wavefronts through LDS

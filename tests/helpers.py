@@ -67,7 +67,13 @@ def attention_errors(got: np.ndarray, ref: np.ndarray):
     return float((num / den).max()), int(mask.sum())
 
 
-def gpu_accept(inp, n_draft=None, greedy="cfg", rng_offset=None, want_probs=True):
+def as_bf16(logits: torch.Tensor) -> torch.Tensor:
+    """The logits as stored by a model that emits bf16 (round to nearest even): input preparation
+    for the bf16 entry point; the oracle gets these values widened back to fp32, which is exact."""
+    return logits.to(torch.bfloat16)
+
+
+def gpu_accept(inp, n_draft=None, greedy="cfg", rng_offset=None, want_probs=True, bf16=False):
     B, S, V = inp.logits.shape
     dev = inp.logits.device
     accept_len = torch.full((B,), -7, dtype=torch.int32, device=dev)
@@ -77,22 +83,24 @@ def gpu_accept(inp, n_draft=None, greedy="cfg", rng_offset=None, want_probs=True
     nd = inp.n_draft if n_draft is None else n_draft
     gr = inp.greedy if isinstance(greedy, str) else greedy
     drafts = inp.draft_tokens[:, :S - 1].contiguous() if S > 1 else None
-    idlm.idlm_isd_accept(inp.logits, drafts, inp.rng_seed, accept_len, new_tokens, n_draft=nd, greedy=gr,
-                         rng_offset=inp.rng_offset if rng_offset is None else rng_offset,
-                         draft_probs=probs if S > 1 else None, workspace=ws)
+    fn = idlm.idlm_isd_accept_bf16 if bf16 else idlm.idlm_isd_accept
+    fn(as_bf16(inp.logits) if bf16 else inp.logits, drafts, inp.rng_seed, accept_len, new_tokens, n_draft=nd,
+       greedy=gr, rng_offset=inp.rng_offset if rng_offset is None else rng_offset,
+       draft_probs=probs if S > 1 else None, workspace=ws)
     torch.cuda.synchronize()
     return dict(accept_len=accept_len.cpu().numpy(), new_tokens=new_tokens.cpu().numpy(),
                 draft_probs=None if probs is None else probs.cpu().numpy()[:, :S - 1].astype(np.float64))
 
 
-def oracle_accept(inp, n_draft=None, greedy="cfg", rng_offset=None):
+def oracle_accept(inp, n_draft=None, greedy="cfg", rng_offset=None, bf16=False):
     S = inp.logits.shape[1]
     nd = inp.n_draft if n_draft is None else n_draft
     nd = to_numpy(nd) if isinstance(nd, torch.Tensor) else nd
     gr = inp.greedy if isinstance(greedy, str) else greedy
     gr = None if gr is None else to_numpy(gr)
     drafts = to_numpy(inp.draft_tokens)[:, :S - 1] if S > 1 else None
-    return oracle.accept(to_numpy(inp.logits), drafts, inp.rng_seed, n_draft=nd, greedy=gr,
+    logits = as_bf16(inp.logits).float() if bf16 else inp.logits
+    return oracle.accept(to_numpy(logits), drafts, inp.rng_seed, n_draft=nd, greedy=gr,
                          rng_offset=inp.rng_offset if rng_offset is None else rng_offset)
 
 

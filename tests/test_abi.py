@@ -86,9 +86,9 @@ def _accept(**kw):
     a = dict(logits=FAKE, drafts=FAKE, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024, ndu=1, nd=None,
              greedy=None, off=0, probs=None, ws=None, ws_bytes=0, stream=None)
     a.update(kw)
-    return idlm.lib().idlm_isd_accept(a["logits"], a["drafts"], a["seed"], a["alen"], a["toks"], a["B"], a["S"],
-                                      a["V"], a["ndu"], a["nd"], a["greedy"], a["off"], a["probs"], a["ws"],
-                                      a["ws_bytes"], a["stream"])
+    fn = getattr(idlm.lib(), a.pop("fn", "idlm_isd_accept"))
+    return fn(a["logits"], a["drafts"], a["seed"], a["alen"], a["toks"], a["B"], a["S"], a["V"], a["ndu"], a["nd"],
+              a["greedy"], a["off"], a["probs"], a["ws"], a["ws_bytes"], a["stream"])
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -99,6 +99,16 @@ def _accept(**kw):
 ])
 def test_accept_rejects_bad_arguments(kw, code):
     assert _accept(**kw) == code
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(logits=None), -1), (dict(alen=None), -1), (dict(toks=None), -1), (dict(drafts=None), -1),
+    (dict(S=0), -2), (dict(S=65), -2), (dict(V=1028), -2), (dict(V=4), -2), (dict(V=0), -2), (dict(ndu=4), -2),
+    (dict(logits=ODD), -4),
+    (dict(), -5), (dict(ws=FAKE, ws_bytes=8), -5), (dict(B=0), 0),
+])
+def test_accept_bf16_rejects_bad_arguments(kw, code):
+    assert _accept(fn="idlm_isd_accept_bf16", **kw) == code
 
 
 def test_accept_empty_batch_and_single_row_without_drafts():
