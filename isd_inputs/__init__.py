@@ -6,11 +6,11 @@ arithmetic (no attention, no acceptance rule, no sampler) and is the only code
 shared by the CPU oracle's tests and the HIP path's tests / benchmark.
 """
 from .configs import CONFIGS, ISDConfig, get_config, n_draft_for_stride
-from .generate import (AcceptInputs, AttentionInputs, make_accept_inputs,
-                       make_attention_inputs, bf16_bits, to_numpy)
+from .generate import (AcceptInputs, AttentionInputs, LoraInputs, make_accept_inputs,
+                       make_attention_inputs, make_lora_inputs, bf16_bits, to_numpy)
 
 __all__ = [
     "CONFIGS", "ISDConfig", "get_config", "n_draft_for_stride",
-    "AcceptInputs", "AttentionInputs", "make_accept_inputs",
-    "make_attention_inputs", "bf16_bits", "to_numpy",
+    "AcceptInputs", "AttentionInputs", "LoraInputs", "make_accept_inputs",
+    "make_attention_inputs", "make_lora_inputs", "bf16_bits", "to_numpy",
 ]

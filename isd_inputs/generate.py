@@ -19,6 +19,8 @@ import torch
 
 from .configs import ISDConfig
 
+BASE_SEED_LORA = 2026041100
+
 
 def bf16_bits(t: torch.Tensor) -> np.ndarray:
     """Bit patterns (uint16) of a bfloat16 tensor, on the host."""
@@ -197,3 +199,38 @@ def make_accept_inputs(cfg: ISDConfig, device="cpu", seed: Optional[int] = None,
         greedy = (torch.rand(B, generator=gen, device=dev) < 0.5).to(torch.uint8)
     rng_seed = (0x9E3779B97F4A7C15 * (cfg.seed if seed is None else seed)) & 0xFFFFFFFFFFFFFFFF
     return AcceptInputs(cfg, logits, drafts, n_draft, greedy, rng_seed, rng_offset)
+
+
+@dataclass
+class LoraInputs:
+    """One linear layer with a low-rank adapter and the tokens of one ISD step (bf16 tensors)."""
+    x: torch.Tensor          # [B*S, d_in] activations, token b*S+j = stride row j of sequence b
+    W: torch.Tensor          # [d_out, d_in] base weight
+    A: torch.Tensor          # [r, d_in]  adapter down-projection
+    Bm: torch.Tensor         # [d_out, r] adapter up-projection
+    n_draft: torch.Tensor    # int32 [B] drafts under introspection per sequence (rows beyond are MASK)
+    S: int
+
+
+def make_lora_inputs(B: int, S: int, d_in: int, d_out: int, r: int, device="cpu", seed: int = 0,
+                     n_draft: Optional[int] = None) -> LoraInputs:
+    """Unit-variance activations; base weight N(0, 1/d_in) so that outputs are O(1); adapter factors
+    N(0, 1/d_in) and N(0, 1/r) so that the residual is of the size of the base output (a trained
+    adapter's is smaller: this makes its errors as visible as the base projection's).  n_draft is
+    uniform on [0, S-1] per sequence unless given (steady state of a stride: (S-1)//2)."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(BASE_SEED_LORA + seed)
+
+    def draw(rows, cols, sigma):
+        return (torch.randn(rows, cols, generator=gen, device=dev, dtype=torch.float32) * sigma).to(torch.bfloat16)
+
+    x = draw(B * S, d_in, 1.0)
+    W = draw(d_out, d_in, d_in ** -0.5)
+    A = draw(r, d_in, d_in ** -0.5)
+    Bm = draw(d_out, r, max(r, 1) ** -0.5)
+    if n_draft is None:
+        nd = torch.randint(0, S, (B,), generator=gen, device=dev, dtype=torch.int32)
+    else:
+        nd = torch.full((B,), n_draft, dtype=torch.int32, device=dev)
+    return LoraInputs(x, W, A, Bm, nd, S)

@@ -63,6 +63,10 @@ def lib() -> C.CDLL:
         L.isd_oracle_kv_append.restype = C.c_int
         L.isd_oracle_commit.argtypes = [C.c_void_p] * 8 + [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 6
         L.isd_oracle_commit.restype = C.c_int
+        L.isd_oracle_gated_lora_linear.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 5 + [C.c_void_p]
+        L.isd_oracle_gated_lora_linear.restype = C.c_int
+        L.isd_oracle_segment_gate.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
+        L.isd_oracle_segment_gate.restype = C.c_int
         _lib = L
     return _lib
 
@@ -294,3 +298,37 @@ def accept_filtered(logits, draft_tokens, rng_seed, *, n_draft, top_k, top_p=1.0
         raise ValueError("isd_oracle_accept_filtered failed: %d" % rc)
     return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, kept=kept, accept_margin=margin,
                 sample_gap=gap, runner_up=runner, proposal_gap=pgap, cut_margin=cut)
+
+
+def gated_lora_linear(x, W, A, Bm, gate, *, sel=None) -> np.ndarray:
+    """h[t] = W x[t] + gate[t] * Bm (A x[t]) in float64 (App. G).  x [T,d_in], W [d_out,d_in], A [r,d_in],
+    Bm [d_out,r]: float32 arrays, or uint16 arrays holding bf16 bits (all the same kind); gate [T].
+    Rows with sel[t] == 0 are not computed (NaN)."""
+    x, W, A, Bm = (np.ascontiguousarray(a) for a in (x, W, A, Bm))
+    dtype = 1 if x.dtype == np.uint16 else 0
+    want = np.uint16 if dtype else np.float32
+    assert all(a.dtype == want for a in (x, W, A, Bm))
+    T, d_in = x.shape
+    d_out, r = Bm.shape
+    assert W.shape == (d_out, d_in) and A.shape == (r, d_in)
+    gate = np.ascontiguousarray(gate, dtype=np.uint8)
+    assert gate.shape == (T,)
+    if sel is not None:
+        sel = np.ascontiguousarray(sel, dtype=np.uint8)
+        assert sel.shape == (T,)
+    h = np.full((T, d_out), np.nan, dtype=np.float64)
+    rc = lib().isd_oracle_gated_lora_linear(_ptr(x), _ptr(W), _ptr(A), _ptr(Bm), _ptr(gate), _ptr(h), T, d_in,
+                                            d_out, r, dtype, _ptr(sel))
+    if rc != 0:
+        raise ValueError("isd_oracle_gated_lora_linear failed: %d" % rc)
+    return h
+
+
+def segment_gate(n_draft, S) -> np.ndarray:
+    """uint8 [B*S]: 1 at the MASK rows (j > n_draft[b]) of every sequence's stride (App. G)."""
+    n_draft = np.ascontiguousarray(n_draft, dtype=np.int32)
+    gate = np.zeros(n_draft.shape[0] * S, dtype=np.uint8)
+    rc = lib().isd_oracle_segment_gate(_ptr(n_draft), _ptr(gate), n_draft.shape[0], S)
+    if rc != 0:
+        raise ValueError("isd_oracle_segment_gate failed: %d" % rc)
+    return gate

@@ -24,6 +24,8 @@
  *     (2): forward -> verify -> trim -> prepare -> forward): the batched scatter
  *     of the stride's K/V rows into the pages (kv_append), and trim-and-commit
  *     plus preparation of the next stride (commit) after Alg. 1's last line.
+ *   - one linear layer of the lossless variant (App. G): base projection for
+ *     every token, low-rank residual only at MASK positions (gated_lora_linear).
  *
  * Pins (tests that check this file against something other than itself) are in
  * tests/test_oracle_*.py; every function here has at least one.
@@ -792,6 +794,75 @@ int isd_oracle_commit(const int32_t* accept_len, const int32_t* new_tokens, int3
     }
     *free_top = top;
     *status = 0;
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Segment-gated LoRA projection (lossless residual ISD)                      */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * One linear layer of the gated-LoRA model (App. G "Per-position computation";
+ * Sec. 3.2 "Lossless ISD with residual adaptation"): token j gets
+ *     h_j = W x_j + 1[j is a MASK position] * B (A x_j)
+ * i.e. the base projection for every token and the low-rank residual only where
+ * the per-token binary gate is set.
+ *
+ * x [T,d_in], W [d_out,d_in], A [r,d_in], Bm [d_out,r], all row-major
+ * contiguous, dtype 0 = fp32, 1 = bf16 bit patterns; gate uint8 [T] (non-zero =
+ * MASK position); h double [T,d_out].  Rows with sel != NULL && sel[t] == 0 are
+ * skipped (left untouched) so that large workloads can be spot-checked.
+ * The low-rank intermediate u = A x_j is kept in double: the paper fixes no
+ * precision for it.
+ */
+int isd_oracle_gated_lora_linear(const void* x, const void* W, const void* A, const void* Bm,
+                                 const uint8_t* gate, double* h, int32_t T, int32_t d_in,
+                                 int32_t d_out, int32_t r, int32_t dtype, const uint8_t* sel)
+{
+    if (T < 0 || d_in < 1 || d_out < 1 || r < 0 || (dtype != 0 && dtype != 1)) return ORACLE_ERR_ARG;
+    if (T == 0) return ORACLE_OK;
+    if (!x || !W || !h || !gate || (r > 0 && (!A || !Bm))) return ORACLE_ERR_ARG;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        if (sel && !sel[t]) continue;
+        double* u = (double*)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+        if (gate[t]) {
+            for (int rho = 0; rho < r; ++rho) {          /* u = A x_t */
+                double acc = 0.0;
+                for (int k = 0; k < d_in; ++k)
+                    acc += load_elem(A, (int64_t)rho * d_in + k, dtype) * load_elem(x, (int64_t)t * d_in + k, dtype);
+                u[rho] = acc;
+            }
+        }
+        for (int o = 0; o < d_out; ++o) {
+            double base = 0.0;                            /* (W x_t)_o */
+            for (int k = 0; k < d_in; ++k)
+                base += load_elem(W, (int64_t)o * d_in + k, dtype) * load_elem(x, (int64_t)t * d_in + k, dtype);
+            double resid = 0.0;                           /* (B u)_o, MASK positions only */
+            if (gate[t])
+                for (int rho = 0; rho < r; ++rho) resid += load_elem(Bm, (int64_t)o * r + rho, dtype) * u[rho];
+            h[(int64_t)t * d_out + o] = base + resid;
+        }
+        free(u);
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * The per-token gate of one ISD stride (App. G, table of position types): of the
+ * S rows of sequence b, rows 0 .. n_draft[b] are fed clean tokens (the exact token
+ * and the drafts under introspection: base weights only, gate 0) and rows beyond
+ * are fed MASK (proposal positions: base + LoRA, gate 1).  gate uint8 [B*S].
+ */
+int isd_oracle_segment_gate(const int32_t* n_draft, uint8_t* gate, int32_t B, int32_t S)
+{
+    if (B < 0 || S < 1 || (B > 0 && (!n_draft || !gate))) return ORACLE_ERR_ARG;
+    for (int b = 0; b < B; ++b) {
+        int nd = n_draft[b];
+        if (nd < 0) nd = 0;
+        if (nd > S - 1) nd = S - 1;
+        for (int j = 0; j < S; ++j) gate[(int64_t)b * S + j] = (uint8_t)(j > nd);
+    }
     return ORACLE_OK;
 }
 
