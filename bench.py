@@ -346,6 +346,32 @@ def main():
                     "frac_hbm": rs_bytes / t_rs / 1e6 / 8000.0}
         del lg16
 
+    # one linear layer of the lossless variant (gated low-rank adapter) on this step's tokens: an attention
+    # projection of the 8B-class model (d_in = d_out = Hq*D) with the paper's rank-128 adapter, MASK rows from
+    # the step's draft counts; and the same layer on the paper's own serving shape (64 sequences, stride N = 4)
+    lora = None
+    if cfg.dtype == "bf16":
+        from isd_inputs import make_lora_inputs
+
+        def lora_case(nseq, rows, nd):
+            d = cfg.Hq * cfg.D
+            li = make_lora_inputs(nseq, rows, d, d, 128, device=dev, seed=1)
+            li.n_draft.copy_(nd)
+            T = nseq * rows
+            h = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+            ws_l = torch.empty(max(256, idlm.idlm_gated_lora_linear_workspace(T, d, d, 128)), dtype=torch.uint8,
+                               device=dev)
+            t_full = timed(lambda: idlm.idlm_gated_lora_linear(li.x, li.W, li.A, li.Bm, h, n_draft=li.n_draft, S=rows,
+                                                               workspace=ws_l), n=20)
+            t_base = timed(lambda: idlm.idlm_gated_lora_linear(li.x, li.W, None, None, h, workspace=ws_l), n=20)
+            masked = int((torch.arange(rows, device=dev)[None, :] > li.n_draft[:, None]).sum().item())
+            flops = 2 * T * d * d + 2 * masked * 128 * (d + d)
+            return {"tokens": T, "mask_tokens": masked, "d_in": d, "d_out": d, "rank": 128, "ms": t_full,
+                    "base_layer_only_ms": t_base, "flops": flops, "TFLOPs": flops / t_full / 1e9,
+                    "frac_mfma": flops / t_full / 1e9 / 2500.0}
+        lora = {"step_tokens": lora_case(B, S, acc.n_draft.clamp(max=S - 1)),
+                "paper_serving_shape_64x7": lora_case(64, 7, torch.full((64,), 3, dtype=torch.int32, device=dev))}
+
     cpu = None
     if args.cpu_sample > 0 and cfg.dtype == "bf16":
         cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
@@ -376,6 +402,7 @@ def main():
         "launch_modes": launch_modes,
         "accept_general": gen,
         "accept_bf16_logits": bf16_acc,
+        "gated_lora_linear": lora,
         "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
                           "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }

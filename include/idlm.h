@@ -315,6 +315,47 @@ int idlm_isd_commit(const int32_t* accept_len, const int32_t* new_tokens, int32_
                     int32_t n_draft_steady, int32_t mask_token, int32_t B, int32_t S, int32_t P,
                     int32_t max_pages_per_seq, void* stream);
 
+/*
+ * idlm_gated_lora_linear - one linear layer of the lossless variant with its low-rank adapter
+ * gated per token (App. G "Per-position computation"; Sec. 3.2 "Lossless ISD with residual
+ * adaptation"):
+ *     h[t,:] = W x[t,:] + gate_t * Bm (A x[t,:])
+ * gate_t = 1 at MASK (proposal) positions, 0 at clean positions (the exact token and the drafts
+ * under introspection), whose outputs are therefore those of the base layer alone, bit for bit:
+ * h[t,:] of a clean token does not depend on A, Bm or on the gates of other tokens.
+ * bf16 operands, fp32 accumulation on the matrix cores, u = A x rounded to bf16 between the two
+ * products, h rounded to bf16 once at the end.
+ *
+ * x        bf16 [T,d_in]      contiguous, 16-byte aligned (all matrices: raw 16-bit patterns).
+ * W        bf16 [d_out,d_in]  base weight, one output feature per row.
+ * A        bf16 [r,d_in]      adapter down-projection; Bm bf16 [d_out,r] its up-projection.
+ *                             Both must be finite.  May be NULL iff r = 0 (plain base layer).
+ * gate     uint8 [T] (non-zero = MASK position), or NULL: then token t = b*S + j of a batch of
+ *          strides of S rows is a MASK position iff j > n_draft[b] (int32 [T/S], clamped to
+ *          [0,S-1]; T % S == 0), the row order of idlm_isd_attention / idlm_isd_accept.
+ * h        bf16 [T,d_out] out.
+ * tile_tokens  0 = choose (the largest token tile that still gives every compute unit a
+ *          workgroup), or 64 / 128 / 256 to force it (tuning, tests).
+ * k_splits     0 = choose, or 1..16: the reduction over d_in is cut into this many parts, one
+ *          workgroup each, summed in a fixed order by a second kernel (few tokens: more
+ *          workgroups for the same weight traffic).  Results do not depend on the number of
+ *          compute units; they may differ in the last bit between different (tile_tokens,
+ *          k_splits), and clean tokens equal the base layer run with the same two values.
+ * workspace    at least idlm_gated_lora_linear_workspace(T,d_in,d_out,r,tile_tokens,k_splits)
+ *          bytes (u and the fp32 partial sums), 256-byte aligned; may be NULL when that is 0.
+ * Supported: d_in a multiple of 64, d_out a multiple of 8, r a multiple of 64 up to 4096 (the
+ * paper's adapters: 128 and 1024); T = 0 is a no-op.  Errors and stream as for the other calls.
+ */
+int idlm_gated_lora_linear(const uint16_t* x, const uint16_t* W, const uint16_t* A, const uint16_t* Bm,
+                           const uint8_t* gate, const int32_t* n_draft, int32_t S, uint16_t* h,
+                           int32_t T, int32_t d_in, int32_t d_out, int32_t r, int32_t tile_tokens,
+                           int32_t k_splits, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace idlm_gated_lora_linear needs (host-only); 0 when none is needed or the
+ * shape is rejected anyway. */
+size_t idlm_gated_lora_linear_workspace(int32_t T, int32_t d_in, int32_t d_out, int32_t r,
+                                        int32_t tile_tokens, int32_t k_splits);
+
 /* Static, NUL-terminated description of a return code (host pointer, never NULL). */
 const char* idlm_strerror(int code);
 

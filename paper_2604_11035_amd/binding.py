@@ -51,6 +51,11 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_bf16.restype = C.c_int
         L.idlm_isd_accept_bf16_ev.argtypes = L.idlm_isd_accept_ev.argtypes
         L.idlm_isd_accept_bf16_ev.restype = C.c_int
+        L.idlm_gated_lora_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp,
+                                             C.c_size_t, vp]
+        L.idlm_gated_lora_linear.restype = C.c_int
+        L.idlm_gated_lora_linear_workspace.argtypes = [i32] * 6
+        L.idlm_gated_lora_linear_workspace.restype = C.c_size_t
         L.idlm_isd_accept_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_workspace.restype = C.c_size_t
         L.idlm_isd_accept_general.argtypes = [vp, vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp,
@@ -307,3 +312,33 @@ def idlm_isd_accept_filtered(logits, draft_tokens, rng_seed, accept_len, new_tok
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_accept_filtered")
+
+
+def idlm_gated_lora_linear_workspace(T, d_in, d_out, r, tile_tokens=0, k_splits=0) -> int:
+    return int(lib().idlm_gated_lora_linear_workspace(T, d_in, d_out, r, tile_tokens, k_splits))
+
+
+def idlm_gated_lora_linear(x, W, A, Bm, h, *, gate=None, n_draft=None, S=1, tile_tokens=0, k_splits=0,
+                           workspace=None, stream=None):
+    """h[t] = W x[t] + gate[t] * Bm (A x[t]) over bf16 tensors x [T,d_in], W [d_out,d_in], A [r,d_in],
+    Bm [d_out,r], h [T,d_out] (see idlm.h).  The gate is a uint8 tensor [T], or the MASK rows of every
+    stride of S rows given int32 n_draft [T/S].  A / Bm may be None for a layer without adapter."""
+    T, d_in = x.shape
+    d_out = W.shape[0]
+    r = 0 if A is None else A.shape[0]
+    assert x.dtype == W.dtype == h.dtype == torch.bfloat16 and x.is_contiguous() and W.is_contiguous()
+    assert W.shape == (d_out, d_in) and h.shape == (T, d_out) and h.is_contiguous()
+    if r:
+        assert A.dtype == Bm.dtype == torch.bfloat16 and A.is_contiguous() and Bm.is_contiguous()
+        assert A.shape == (r, d_in) and Bm.shape == (d_out, r)
+    if gate is not None:
+        assert gate.dtype == torch.uint8 and gate.numel() == T and gate.is_contiguous()
+    if n_draft is not None:
+        assert n_draft.dtype == torch.int32 and n_draft.numel() * S == T and n_draft.is_contiguous()
+    rc = lib().idlm_gated_lora_linear(_ptr(x), _ptr(W), _ptr(A), _ptr(Bm), _ptr(gate), _ptr(n_draft), S, _ptr(h),
+                                      T, d_in, d_out, r, tile_tokens, k_splits, _ptr(workspace),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_gated_lora_linear")
+    return h

@@ -9,7 +9,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libidlm_isd.so"
-SOURCES = ["isd_attention.hip", "isd_accept.hip", "isd_accept_general.hip", "isd_accept_filtered.hip", "isd_loop.hip", "idlm_misc.hip"]
+SOURCES = ["isd_attention.hip", "isd_accept.hip", "isd_accept_general.hip", "isd_accept_filtered.hip", "isd_loop.hip", "isd_lora.hip", "idlm_misc.hip"]
 # Packed fp32 VALU forms are switched off for all device code (they have produced wrong
 # results on the target machines); the host pass does not know the feature and says so.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",

@@ -226,3 +226,36 @@ def test_filtered_accept_workspace_and_empty_batch():
     assert _filtered(B=0) == 0
     assert idlm.idlm_isd_accept_filtered_workspace(256, 16, 151936) == 256 * 16 * 64 * 8
     assert idlm.idlm_isd_accept_filtered_workspace(4, 4, 1023) == 0
+
+
+def _lora(**kw):
+    a = dict(x=FAKE, W=FAKE, A=FAKE, Bm=FAKE, gate=FAKE, nd=None, S=1, h=FAKE, T=32, d_in=256, d_out=512, r=128, tile=0,
+             splits=0, ws=None, ws_bytes=0, stream=None)
+    a.update(kw)
+    return idlm.lib().idlm_gated_lora_linear(a["x"], a["W"], a["A"], a["Bm"], a["gate"], a["nd"], a["S"], a["h"], a["T"],
+                                             a["d_in"], a["d_out"], a["r"], a["tile"], a["splits"], a["ws"], a["ws_bytes"],
+                                             a["stream"])
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(x=None), -1), (dict(W=None), -1), (dict(h=None), -1), (dict(A=None), -1), (dict(Bm=None), -1),
+    (dict(gate=None, nd=None), -1),
+    (dict(d_in=96), -2), (dict(d_in=0), -2), (dict(d_out=12), -2), (dict(d_out=0), -2), (dict(r=32), -2), (dict(r=8192), -2),
+    (dict(T=-1), -2), (dict(tile=32), -2), (dict(splits=17), -2), (dict(splits=-1), -2),
+    (dict(gate=None, nd=FAKE, S=5), -2),            # T = 32 is not a whole number of strides of 5 rows
+    (dict(gate=None, nd=FAKE, S=0), -2),
+    (dict(x=ODD), -4), (dict(W=ODD), -4), (dict(h=ODD), -4), (dict(A=ODD), -4),
+    (dict(), -5), (dict(ws=FAKE, ws_bytes=64), -5),
+    (dict(T=0), 0),
+])
+def test_gated_lora_rejects_bad_arguments(kw, code):
+    assert _lora(**kw) == code
+
+
+def test_gated_lora_workspace_is_host_only():
+    w = idlm.idlm_gated_lora_linear_workspace
+    assert w(4096, 4096, 4096, 128, 0, 0) == 4096 * 128 * 2 + 4 * 4096 * 128 * 4     # u and the four partial sums of the shrink
+    assert w(4096, 4096, 4096, 0, 256, 1) == 0                                       # plain base layer, one K part
+    assert w(448, 4096, 4096, 128, 128, 4) >= 448 * 128 * 2 + 4 * 448 * 4096 * 4
+    assert w(448, 4096, 4096, 128, 0, 0) % 256 == 0
+    assert w(32, 96, 512, 128, 0, 0) == 0 and w(32, 256, 512, 128, 32, 0) == 0 and w(32, 256, 512, 128, 0, 17) == 0
