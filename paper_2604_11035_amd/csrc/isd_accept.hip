@@ -11,6 +11,20 @@
 
 namespace idlm {
 
+struct ChainResult {   // what the sampling pass needs to know about a sequence
+    int row;           // stride row r that emits the fresh token, or -1 (greedy: nothing to sample)
+    int excluded;      // token id removed from the sample (the rejected draft), or -1
+    float skip_below;  // logits below this cannot win the Gumbel-max of row r (-inf: no such bound)
+    int pad;
+};
+
+// The Gumbel noise of a 24-bit uniform lies in [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355].
+// With a the row's arg-max (not excluded), l_a + g_a >= m - 2.8115, so an element with
+// l_i < m - 19.5 has l_i + g_i < m - 19.5 + 16.6355 < l_a + g_a whatever the noise: it is skipped
+// without evaluating its noise, and the arg-max is exactly that of the full evaluation (0.05 of
+// slack covers the rounding of the noise and of the sums).
+constexpr float kGumbelSpan = 19.5f;
+
 struct AcceptWorkspace {
     size_t stats_off, keys_off, chain_off, total;
 };
@@ -22,16 +36,13 @@ static AcceptWorkspace layout(int32_t B, int32_t S, const AcceptPlan& p)
     size_t stats = (size_t)B * S * p.nsplit * sizeof(RowPartial);
     w.keys_off = align256(stats);
     w.chain_off = w.keys_off + align256((size_t)B * sizeof(unsigned long long));   // one arg-max key per sequence
-    w.total = w.chain_off + align256((size_t)B * 2 * sizeof(int32_t));
+    w.total = w.chain_off + align256((size_t)B * sizeof(ChainResult));
     return w;
 }
 
 // ---- pass 2: accept chain and proposals, one wavefront per sequence ---------------------------
 
-struct ChainResult {   // what the sampling pass needs to know about a sequence
-    int row;           // stride row r that emits the fresh token, or -1 (greedy: nothing to sample)
-    int excluded;      // token id removed from the sample (the rejected draft), or -1
-};
+
 
 template <bool BF16>
 __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
@@ -49,13 +60,14 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
     const int ncol = S - 1;
 
     int a = 0, ok = 1, x = -1;
-    float p = 0.f;
+    float p = 0.f, m_row = -INFINITY;
     if (tid < S) {
         const int row = b * S + tid;
         const RowPartial* sp = stats + (size_t)row * nsplit;
         float m = sp[0].m, z = sp[0].z;
         a = sp[0].arg;
         for (int k = 1; k < nsplit; ++k) combine_stats(m, z, a, sp[k].m, sp[k].z, sp[k].arg);
+        m_row = m;
         if (tid < n_d) {
             x = draft_tokens[(size_t)b * ncol + tid];
             if (x >= 0 && x < V) {
@@ -76,6 +88,7 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
     const int r = failed ? (int)__builtin_ctzll(failed) : n_d;
     const int a_r = __shfl(a, r);
     const int x_r = __shfl(x, r);
+    const float m_r = __shfl(m_row, r);
     if (tid < S) {
         int tok;
         if (tid < r) tok = x;
@@ -89,6 +102,8 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
         ChainResult cr;
         cr.row = is_greedy ? -1 : r;
         cr.excluded = (r < n_d) ? x_r : -1;
+        cr.skip_below = (cr.excluded == a_r) ? -INFINITY : m_r - kGumbelSpan;   // the bound needs the arg-max in the sample
+        cr.pad = 0;
         chain[b] = cr;
         keys[b] = 0ull;   // "nothing sampled yet"
     }
@@ -122,19 +137,32 @@ __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
     const int fend = min(V, (c + 1) * gchunk) / N;
     float best = -INFINITY;
     int bidx = INT_MAX;
-    for (int f = fbeg + tid; f < fend; f += 256) {
-        float e[N];
-        LV::unpack(pv[f], e);
+    const float skip_below = cr.skip_below;
+    for (int f0 = fbeg + tid; f0 < fend; f0 += 4 * 256) {   // four loads in flight, then the noise of what can win
+        raw_t v[4];
 #pragma unroll
-        for (int h = 0; h < N / 4; ++h) {   // one Philox block per four consecutive elements
-            const int i0 = f * N + h * 4;
-            const uint4 w = philox4x32_10(make_uint4((uint32_t)(i0 >> 2), row, 1u, rng_offset), key);
-            const float s0 = e[h * 4] + gumbel(w.x), s1 = e[h * 4 + 1] + gumbel(w.y);
-            const float s2 = e[h * 4 + 2] + gumbel(w.z), s3 = e[h * 4 + 3] + gumbel(w.w);
-            if (i0 != excluded && s0 > best) { best = s0; bidx = i0; }
-            if (i0 + 1 != excluded && s1 > best) { best = s1; bidx = i0 + 1; }
-            if (i0 + 2 != excluded && s2 > best) { best = s2; bidx = i0 + 2; }
-            if (i0 + 3 != excluded && s3 > best) { best = s3; bidx = i0 + 3; }
+        for (int u = 0; u < 4; ++u) {
+            const int f = f0 + u * 256;
+            v[u] = pv[f < fend ? f : f0];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int f = f0 + u * 256;
+            if (f >= fend) break;
+            float e[N];
+            LV::unpack(v[u], e);
+#pragma unroll
+            for (int h = 0; h < N / 4; ++h) {   // one Philox block per four consecutive elements
+                if (fmaxf(fmaxf(e[h * 4], e[h * 4 + 1]), fmaxf(e[h * 4 + 2], e[h * 4 + 3])) < skip_below) continue;
+                const int i0 = f * N + h * 4;
+                const uint4 w = philox4x32_10(make_uint4((uint32_t)(i0 >> 2), row, 1u, rng_offset), key);
+                const float s0 = e[h * 4] + gumbel(w.x), s1 = e[h * 4 + 1] + gumbel(w.y);
+                const float s2 = e[h * 4 + 2] + gumbel(w.z), s3 = e[h * 4 + 3] + gumbel(w.w);
+                if (i0 != excluded && s0 > best) { best = s0; bidx = i0; }
+                if (i0 + 1 != excluded && s1 > best) { best = s1; bidx = i0 + 1; }
+                if (i0 + 2 != excluded && s2 > best) { best = s2; bidx = i0 + 2; }
+                if (i0 + 3 != excluded && s3 > best) { best = s3; bidx = i0 + 3; }
+            }
         }
     }
 #pragma unroll
