@@ -19,10 +19,12 @@ struct ChainResult {   // what the sampling pass needs to know about a sequence
 };
 
 // The Gumbel noise of a 24-bit uniform lies in [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355].
-// With a the row's arg-max (not excluded), l_a + g_a >= m - 2.8115, so an element with
-// l_i < m - 19.5 has l_i + g_i < m - 19.5 + 16.6355 < l_a + g_a whatever the noise: it is skipped
-// without evaluating its noise, and the arg-max is exactly that of the full evaluation (0.05 of
-// slack covers the rounding of the noise and of the sums).
+// If some element j that takes part in the sample has l_j = c, the winner scores at least c - 2.8115, so
+// an element with l_i < c - 19.5 has l_i + g_i < c - 19.5 + 16.6355 < l_j + g_j whatever the noise: it
+// is skipped without evaluating its noise, and the arg-max is exactly that of the full evaluation
+// (0.05 of slack covers the rounding of the noise and of the sums).  c is the row maximum, or, when the
+// arg-max itself is the excluded token (the usual rejection), the value of another element that the
+// row-statistics pass brings along (RowPartial::m2).
 constexpr float kGumbelSpan = 19.5f;
 
 struct AcceptWorkspace {
@@ -60,14 +62,18 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
     const int ncol = S - 1;
 
     int a = 0, ok = 1, x = -1;
-    float p = 0.f, m_row = -INFINITY;
+    float p = 0.f, m_row = -INFINITY, m2_row = -INFINITY;
     if (tid < S) {
         const int row = b * S + tid;
         const RowPartial* sp = stats + (size_t)row * nsplit;
-        float m = sp[0].m, z = sp[0].z;
+        float m = sp[0].m, z = sp[0].z, second = sp[0].m2;
         a = sp[0].arg;
-        for (int k = 1; k < nsplit; ++k) combine_stats(m, z, a, sp[k].m, sp[k].z, sp[k].arg);
+        for (int k = 1; k < nsplit; ++k) {
+            second = combine_second(m, second, sp[k].m, sp[k].m2);
+            combine_stats(m, z, a, sp[k].m, sp[k].z, sp[k].arg);
+        }
         m_row = m;
+        m2_row = second;
         if (tid < n_d) {
             x = draft_tokens[(size_t)b * ncol + tid];
             if (x >= 0 && x < V) {
@@ -89,6 +95,7 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
     const int a_r = __shfl(a, r);
     const int x_r = __shfl(x, r);
     const float m_r = __shfl(m_row, r);
+    const float m2_r = __shfl(m2_row, r);
     if (tid < S) {
         int tok;
         if (tid < r) tok = x;
@@ -102,7 +109,7 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
         ChainResult cr;
         cr.row = is_greedy ? -1 : r;
         cr.excluded = (r < n_d) ? x_r : -1;
-        cr.skip_below = (cr.excluded == a_r) ? -INFINITY : m_r - kGumbelSpan;   // the bound needs the arg-max in the sample
+        cr.skip_below = ((cr.excluded == a_r) ? m2_r : m_r) - kGumbelSpan;
         cr.pad = 0;
         chain[b] = cr;
         keys[b] = 0ull;   // "nothing sampled yet"

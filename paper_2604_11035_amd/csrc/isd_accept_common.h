@@ -26,8 +26,15 @@ struct RowPartial {   // statistics of one slice of one logit row
     float m;          // maximum (true value, compared exactly)
     float z;          // sum of 2^(l*k - ref_k(m, k))
     int arg;          // lowest index attaining m (INT_MAX if the slice is empty)
-    int pad;
+    float m2;         // a value attained by an element other than `arg`, or -inf: the largest of the other
+                      // threads' maxima, a lower bound of the second-largest logit that costs nothing per element
 };
+
+// (m, m2) of the union of two disjoint element sets, to be called before m is updated
+__device__ __forceinline__ float combine_second(float m, float m2, float mo, float m2o)
+{
+    return fmaxf(fmaxf(m2, m2o), fminf(m, mo));
+}
 
 // Best (score, index) of a sampled row as one 64-bit key whose unsigned order is "higher score
 // first, then lower index": workgroups of a row combine with a single atomic max, no fences.
@@ -169,22 +176,28 @@ __global__ __launch_bounds__(256) void isd_row_stats_kernel(const void* __restri
     }
 
     // wavefront reduction, then the four wavefronts through LDS
+    float second = -INFINITY;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        const float m2 = __shfl_xor(m, off);
-        const float z2 = __shfl_xor(z, off);
-        const int a2 = __shfl_xor(arg, off);
-        combine_stats(m, z, arg, m2, z2, a2, k);
+        const float mo = __shfl_xor(m, off);
+        const float zo = __shfl_xor(z, off);
+        const int ao = __shfl_xor(arg, off);
+        const float so = __shfl_xor(second, off);
+        second = combine_second(m, second, mo, so);
+        combine_stats(m, z, arg, mo, zo, ao, k);
     }
-    __shared__ float sm[4], sz[4];
+    __shared__ float sm[4], sz[4], ss[4];
     __shared__ int sa[4];
     const int w = tid >> 6;
-    if ((tid & 63) == 0) { sm[w] = m; sz[w] = z; sa[w] = arg; }
+    if ((tid & 63) == 0) { sm[w] = m; sz[w] = z; sa[w] = arg; ss[w] = second; }
     __syncthreads();
     if (tid == 0) {
-        for (int q = 1; q < 4; ++q) combine_stats(m, z, arg, sm[q], sz[q], sa[q], k);
+        for (int q = 1; q < 4; ++q) {
+            second = combine_second(m, second, sm[q], ss[q]);
+            combine_stats(m, z, arg, sm[q], sz[q], sa[q], k);
+        }
         RowPartial out;
-        out.m = m; out.z = z; out.arg = arg; out.pad = 0;
+        out.m = m; out.z = z; out.arg = arg; out.m2 = second;
         stats[(size_t)row * nsplit + c] = out;
     }
 }
