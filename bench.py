@@ -188,8 +188,13 @@ def main():
     def avg(which, a, b):
         return sum(hev.elapsed_ms(e[which][a], e[which][b]) for e in events) / len(events)
 
+    def spread(which, a, b):
+        v = sorted(hev.elapsed_ms(e[which][a], e[which][b]) for e in events)
+        return {"min_ms": v[0], "median_ms": v[len(v) // 2], "max_ms": v[-1], "samples": len(v)}
+
     t_att_main, t_att_merge = avg(0, 0, 1), avg(0, 1, 2)
     t_acc_stats, t_acc_final = avg(1, 0, 1), avg(1, 1, 2)
+    spreads = {"isd_attention_bf16_kernel": spread(0, 0, 1), "isd_row_stats_kernel": spread(1, 0, 1)}
     for ea, eb in events:
         hev.destroy(ea + eb)
 
@@ -208,6 +213,15 @@ def main():
             "ms": t_acc_stats, "algorithmic_bytes": acc_bytes, "GBps": acc_bytes / t_acc_stats / 1e6,
             "frac_hbm": acc_bytes / t_acc_stats / 1e6 / HBM_PEAK_GBS},
         "isd_accept_chain+sample+emit_kernels": {"ms": t_acc_final},
+    }
+    for name, sp in spreads.items():
+        kernels[name].update(sp)
+    t_att_call, t_acc_call = t_att_main + t_att_merge, t_acc_stats + t_acc_final
+    per_call = {
+        "attention_positions_per_s": B * S / (t_att_call / 1e3), "accept_positions_per_s": B * S / (t_acc_call / 1e3),
+        # context only: a forward of the 8B-class model the paper converts has 36 attention layers per acceptance
+        # pass; its linear layers are not part of this figure
+        "model_shaped_positions_per_s_36_attention_layers_no_gemms": B * S / ((36 * t_att_call + t_acc_call) / 1e3),
     }
     if t_att_main >= t_acc_stats:
         dom, dom_name, dom_key = kernels["isd_attention_bf16_kernel"], "isd_attention_bf16_kernel", "attention"
@@ -239,6 +253,8 @@ def main():
     t_copy = timed(lambda: idlm.idlm_stream_copy(probe, probe_dst))
     stream_probe = {"read_GBps": probe.numel() / t_read / 1e6, "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6,
               "bytes": probe.numel()}
+    for name in ("isd_attention_bf16_kernel", "isd_row_stats_kernel"):
+        kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / stream_probe["read_GBps"]
     del probe, probe_dst
 
     # the same step launched without the timing hooks, and replayed from a captured HIP graph (the
@@ -397,6 +413,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "per_call": per_call,
         "stream_ceiling": stream_probe,
         "between_steps": loop_kernels,
         "launch_modes": launch_modes,
