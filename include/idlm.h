@@ -19,6 +19,7 @@
  *     ceil(ctx_lens[b]/P) <= max_pages_per_seq; block_table[b][p] in
  *     [0,num_pages) for p < ceil(ctx_lens[b]/P) (entries beyond that are never
  *     read); draft token ids in [0,V); n_draft[b] in [0,S-1]; logits hold no NaN.
+ *     (idlm_isd_validate checks them on request).
  *     A broken precondition gives meaningless results, never an access outside
  *     the caller's buffers as far as the sizes passed on the host allow to tell
  *     (context lengths are cut at the table row, page ids are forced into the pool).
@@ -44,7 +45,17 @@ enum {
     IDLM_ERR_DTYPE = -3,     /* unknown dtype code, or dtype/shape combination not supported */
     IDLM_ERR_ALIGN = -4,     /* a pointer or stride breaks the alignment the kernels need */
     IDLM_ERR_WORKSPACE = -5, /* workspace missing or smaller than the *_workspace() size */
-    IDLM_ERR_LAUNCH = -6     /* the HIP runtime refused the launch (no device, bad stream, ...) */
+    IDLM_ERR_LAUNCH = -6,    /* the HIP runtime refused the launch (no device, bad stream, ...) */
+    IDLM_ERR_CONTENT = -7    /* idlm_isd_validate only: a device array breaks a precondition */
+};
+
+/* Bits of report[0] of idlm_isd_validate. */
+enum {
+    IDLM_BAD_CTX_SHORT = 1,  /* ctx_lens[b] < S */
+    IDLM_BAD_CTX_LONG = 2,   /* ctx_lens[b] > max_pages_per_seq * P */
+    IDLM_BAD_PAGE_ID = 4,    /* a block-table entry the step reads is outside [0, num_pages) */
+    IDLM_BAD_N_DRAFT = 8,    /* n_draft[b] outside [0, S-1] */
+    IDLM_BAD_DRAFT_ID = 16   /* a draft token id the step reads is outside [0, V) */
 };
 
 enum {
@@ -355,6 +366,27 @@ int idlm_gated_lora_linear(const uint16_t* x, const uint16_t* W, const uint16_t*
  * shape is rejected anyway. */
 size_t idlm_gated_lora_linear_workspace(int32_t T, int32_t d_in, int32_t d_out, int32_t r,
                                         int32_t tile_tokens, int32_t k_splits);
+
+/*
+ * idlm_isd_validate - debug aid: checks the CONTENTS of the device arrays that the calls of one
+ * step (idlm_isd_attention, idlm_isd_kv_append, the idlm_isd_accept family) take as
+ * preconditions, and WAITS for the result (it synchronises `stream`; not for graph capture or
+ * the serving loop).
+ *
+ * block_table, ctx_lens, S, B, P, num_pages, max_pages_per_seq: as for idlm_isd_attention; either
+ *          pointer may be NULL to skip the checks that need it.
+ * draft_tokens int32 [B,S-1], n_draft int32 [B] or NULL (n_draft_uniform), V: as for
+ *          idlm_isd_accept; draft_tokens may be NULL to skip the id check.
+ * report   DEVICE int32[4], written: [0] = OR of the IDLM_BAD_* bits found, [1] = lowest sequence
+ *          index with a finding (-1: none), [2], [3] = 0.
+ * host_report  HOST int32[4] or NULL: receives the same four words.
+ * Returns IDLM_OK when nothing was found, IDLM_ERR_CONTENT otherwise (or the usual codes for bad
+ * host-visible arguments; S up to 64 as for the acceptance calls).
+ */
+int idlm_isd_validate(const int32_t* block_table, const int32_t* ctx_lens, int32_t S, int32_t B, int32_t P,
+                      int32_t num_pages, int32_t max_pages_per_seq, const int32_t* draft_tokens,
+                      const int32_t* n_draft, int32_t n_draft_uniform, int32_t V, int32_t* report,
+                      int32_t* host_report, void* stream);
 
 /* Static, NUL-terminated description of a return code (host pointer, never NULL). */
 const char* idlm_strerror(int code);

@@ -51,6 +51,8 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_bf16.restype = C.c_int
         L.idlm_isd_accept_bf16_ev.argtypes = L.idlm_isd_accept_ev.argtypes
         L.idlm_isd_accept_bf16_ev.restype = C.c_int
+        L.idlm_isd_validate.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, vp]
+        L.idlm_isd_validate.restype = C.c_int
         L.idlm_gated_lora_linear.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, vp,
                                              C.c_size_t, vp]
         L.idlm_gated_lora_linear.restype = C.c_int
@@ -342,3 +344,27 @@ def idlm_gated_lora_linear(x, W, A, Bm, h, *, gate=None, n_draft=None, S=1, tile
     if rc != 0:
         raise IdlmError(rc, "idlm_gated_lora_linear")
     return h
+
+
+def idlm_isd_validate(block_table, ctx_lens, S, *, P, num_pages, draft_tokens=None, n_draft=None, V=1, report=None,
+                      stream=None):
+    """Checks the device arrays of one step against the calls' preconditions and waits for the answer
+    (see idlm.h).  Returns (return code, [bits, first bad sequence, 0, 0])."""
+    B = int(ctx_lens.numel()) if ctx_lens is not None else int(n_draft.numel() if isinstance(n_draft, torch.Tensor)
+                                                               else draft_tokens.shape[0])
+    max_pages = 0 if block_table is None else block_table.shape[1]
+    for t in (block_table, ctx_lens, draft_tokens):
+        assert t is None or (t.dtype == torch.int32 and t.is_contiguous())
+    nd_ptr, nd_uni = None, 0
+    if isinstance(n_draft, torch.Tensor):
+        assert n_draft.dtype == torch.int32 and n_draft.numel() == B
+        nd_ptr = _ptr(n_draft)
+    elif n_draft is not None:
+        nd_uni = int(n_draft)
+    if report is None:
+        dev = next(t for t in (ctx_lens, block_table, draft_tokens) if t is not None).device
+        report = torch.empty(4, dtype=torch.int32, device=dev)
+    host = (C.c_int32 * 4)()
+    rc = lib().idlm_isd_validate(_ptr(block_table), _ptr(ctx_lens), S, B, P, num_pages, max_pages, _ptr(draft_tokens),
+                                 nd_ptr, nd_uni, V, _ptr(report), host, _stream(stream))
+    return rc, list(host)

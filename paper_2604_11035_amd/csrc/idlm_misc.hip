@@ -44,11 +44,81 @@ extern "C" const char* idlm_strerror(int code)
         case IDLM_ERR_ALIGN: return "a pointer or stride is not aligned as required";
         case IDLM_ERR_WORKSPACE: return "workspace missing or too small";
         case IDLM_ERR_LAUNCH: return "the HIP runtime refused the launch";
+        case IDLM_ERR_CONTENT: return "a device array breaks a precondition (see the report of idlm_isd_validate)";
         default: return "unknown idlm error code";
     }
 }
 
 extern "C" int idlm_version(void) { return IDLM_VERSION; }
+
+namespace idlm {
+
+__global__ void validate_clear_kernel(int32_t* report)
+{
+    if (threadIdx.x < 4) report[threadIdx.x] = threadIdx.x == 1 ? INT32_MAX : 0;
+}
+
+// One wavefront per sequence: its length, the page ids it will read, its draft count and draft ids.
+__global__ __launch_bounds__(64) void validate_kernel(const int32_t* __restrict__ block_table,
+                                                     const int32_t* __restrict__ ctx_lens, int S, int B, int P,
+                                                     int num_pages, int max_pages,
+                                                     const int32_t* __restrict__ draft_tokens,
+                                                     const int32_t* __restrict__ n_draft, int n_draft_uniform, int V,
+                                                     int32_t* report)
+{
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    int bad = 0;
+    if (ctx_lens) {
+        const int ctx = ctx_lens[b];
+        if (ctx < S) bad |= IDLM_BAD_CTX_SHORT;
+        if (block_table && (int64_t)ctx > (int64_t)max_pages * P) bad |= IDLM_BAD_CTX_LONG;
+        if (block_table && ctx > 0) {
+            const int npages = (int)min((int64_t)max_pages, ((int64_t)ctx + P - 1) / P);
+            for (int pg = lane; pg < npages; pg += 64) {
+                const int id = block_table[(size_t)b * max_pages + pg];
+                if (id < 0 || id >= num_pages) bad |= IDLM_BAD_PAGE_ID;
+            }
+        }
+    }
+    int nd = n_draft ? n_draft[b] : n_draft_uniform;
+    if (nd < 0 || nd > S - 1) { bad |= IDLM_BAD_N_DRAFT; nd = max(0, min(nd, S - 1)); }
+    if (draft_tokens && lane < nd) {
+        const int x = draft_tokens[(size_t)b * (S - 1) + lane];
+        if (x < 0 || x >= V) bad |= IDLM_BAD_DRAFT_ID;
+    }
+    if (bad) {
+        atomicOr(&report[0], bad);
+        atomicMin(&report[1], b);
+    }
+}
+
+}  // namespace idlm
+
+extern "C" int idlm_isd_validate(const int32_t* block_table, const int32_t* ctx_lens, int32_t S, int32_t B, int32_t P,
+                                 int32_t num_pages, int32_t max_pages_per_seq, const int32_t* draft_tokens,
+                                 const int32_t* n_draft, int32_t n_draft_uniform, int32_t V, int32_t* report,
+                                 int32_t* host_report, void* stream)
+{
+    if (B < 0 || S < 1 || S > 64 || P < 1 || num_pages < 0 || max_pages_per_seq < 0 || V < 1) return IDLM_ERR_SHAPE;
+    if (!report) return IDLM_ERR_NULL;
+    if (B == 0) {
+        if (host_report) { host_report[0] = 0; host_report[1] = -1; host_report[2] = host_report[3] = 0; }
+        return IDLM_OK;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(idlm::validate_clear_kernel, dim3(1), dim3(64), 0, st, report);
+    hipLaunchKernelGGL(idlm::validate_kernel, dim3((unsigned)B), dim3(64), 0, st, block_table, ctx_lens, S, B, P, num_pages,
+                       max_pages_per_seq, draft_tokens, n_draft, n_draft_uniform, V, report);
+    int32_t host[4] = {0, 0, 0, 0};
+    if (hipMemcpyAsync(host, report, sizeof host, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess)
+        return IDLM_ERR_LAUNCH;
+    if (host[1] == INT32_MAX) host[1] = -1;
+    if (host_report) { host_report[0] = host[0]; host_report[1] = host[1]; host_report[2] = host[2]; host_report[3] = host[3]; }
+    return host[0] ? IDLM_ERR_CONTENT : IDLM_OK;
+}
 
 extern "C" int idlm_stream_copy(const void* src, void* dst, size_t n_bytes, void* stream)
 {

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_error_strings():
     assert idlm.idlm_version() == 100
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         msg = idlm.idlm_strerror(code)
         assert msg and msg not in seen
         seen.add(msg)
@@ -259,3 +259,13 @@ def test_gated_lora_workspace_is_host_only():
     assert w(448, 4096, 4096, 128, 128, 4) >= 448 * 128 * 2 + 4 * 448 * 4096 * 4
     assert w(448, 4096, 4096, 128, 0, 0) % 256 == 0
     assert w(32, 96, 512, 128, 0, 0) == 0 and w(32, 256, 512, 128, 32, 0) == 0 and w(32, 256, 512, 128, 0, 17) == 0
+
+
+def test_validate_checks_host_arguments_first():
+    v = idlm.lib().idlm_isd_validate
+    host = (C.c_int32 * 4)(9, 9, 9, 9)
+    args = lambda **kw: [kw.get("table", FAKE), kw.get("ctx", FAKE), kw.get("S", 4), kw.get("B", 2), 16, 10, 4, FAKE, None, 1,
+                         1024, kw.get("report", FAKE), host, None]
+    assert v(*args(report=None)) == -1
+    assert v(*args(S=0)) == -2 and v(*args(S=65)) == -2 and v(*args(B=-1)) == -2
+    assert v(*args(B=0)) == 0 and list(host) == [0, -1, 0, 0]
