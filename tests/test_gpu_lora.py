@@ -149,3 +149,40 @@ def test_wide_adapter_and_wide_layer():
     inp = make_lora_inputs(12, 9, 1024, 3072, 1024, device=DEV, seed=5)
     gate = oracle.segment_gate(to_numpy(inp.n_draft), 9)
     _check(inp, _run(inp), gate, rows=np.arange(0, 108, 5))
+
+
+@pytest.mark.parametrize("B,S,tile,splits", [(24, 7, 0, 0), (70, 9, 256, 1)])
+def test_replays_from_a_captured_graph(B, S, tile, splits):
+    """The call allocates nothing and never synchronises: captured once, replayed with the tokens and
+    draft counts refreshed in place, every replay bit-identical to an eager call on the same inputs."""
+    import paper_2604_11035_amd as idlm
+    d_in, d_out, r = 512, 520, 128
+    inp = make_lora_inputs(B, S, d_in, d_out, r, device=DEV, seed=11)
+    T = B * S
+    h = torch.zeros(T, d_out, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(max(256, idlm.idlm_gated_lora_linear_workspace(T, d_in, d_out, r, tile, splits)), dtype=torch.uint8,
+                     device=DEV)
+    call = lambda stream=None: idlm.idlm_gated_lora_linear(inp.x, inp.W, inp.A, inp.Bm, h, n_draft=inp.n_draft, S=S,
+                                                           tile_tokens=tile, k_splits=splits, workspace=ws, stream=stream)
+    call()                                   # first eager call (sets the kernels' LDS limits outside the capture)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(side)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    for rep in range(4):
+        inp.x.copy_(torch.randn(T, d_in, generator=gen, device=DEV).to(torch.bfloat16))
+        inp.n_draft.copy_(torch.randint(0, S, (B,), generator=gen, device=DEV, dtype=torch.int32))
+        h.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = h.clone()
+        h.zero_()
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(replayed.view(torch.int16), h.view(torch.int16)), rep
+        assert bool(replayed.float().abs().sum() > 0)
+        _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()      # unrelated eager work between replays
