@@ -511,7 +511,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                         for (int j = 0; j < 4; ++j) {
                             if (row0 + j < M) {
                                 uint16_t* op = p.out + ((size_t)(b * S + ip) * p.Hq + kvh * G + gq) * 128 + (4 * g + q4) * 8;
-                                *reinterpret_cast<u32x4*>(op) = c[j];
+                                __builtin_nontemporal_store(c[j], reinterpret_cast<u32x4*>(op));
                             }
                             if (++gq == G) { gq = 0; ++ip; }
                         }
