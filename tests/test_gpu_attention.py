@@ -76,6 +76,16 @@ def test_long_context_stride_sweep_sampled(S):
         assert (inp.ctx_lens == 32768).all()
 
 
+@pytest.mark.parametrize("S", [1, 16])
+def test_long_context_full_batch_sampled(S):
+    """The long-context workload at its full size (B=32, 32 768 tokens each, 4.3 GB of K/V) in the launch
+    configuration the benchmark's stride sweep times; the oracle computes a seeded sample of (sequence, KV head)
+    pairs.  S = 1 is one row group per KV head, S = 16 two (128 rows share a head)."""
+    cfg = get_config("long32k", S=S)
+    inp = make_attention_inputs(cfg, device=DEV)
+    _check(inp, sel=_sample_pairs(cfg.B, cfg.Hkv, 3, 100 + S))
+
+
 def _manual(B, S, Hq, Hkv, ctx, dtype=torch.bfloat16, D=128, seed=0, token_major=False, extra_pages=2):
     """Small hand-shaped inputs (ragged contexts, paddings) with NaN-poisoned unused slots."""
     g = torch.Generator(device="cpu").manual_seed(seed)
