@@ -126,6 +126,8 @@ def main():
     ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
     ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
+    ap.add_argument("--k-operand-order", type=int, default=1,
+                    help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -159,10 +161,16 @@ def main():
 
     hev = HipEvents()
     stream = torch.cuda.current_stream()
+    kop = bool(args.k_operand_order) and cfg.dtype == "bf16"
+    k_gpu = att.k_cache
+    if kop:   # the same pool, pages permuted once (what idlm_isd_kv_append maintains when given the same option)
+        from isd_inputs import k_pages_in_operand_order
+        k_gpu = k_pages_in_operand_order(att.k_cache)
 
     def step(i, ev_att=None, ev_acc=None):
-        idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
-                                num_workgroups=args.workgroups, workspace=ws_att, stream=stream, events=ev_att)
+        idlm.idlm_isd_attention(att.q, k_gpu, att.v_cache, att.block_table, att.ctx_lens, S, out,
+                                num_workgroups=args.workgroups, workspace=ws_att, stream=stream, events=ev_att,
+                                k_operand_order=kop)
         idlm.idlm_isd_accept(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft,
                              greedy=acc.greedy, rng_offset=i, draft_probs=draft_probs if S > 1 else None,
                              workspace=ws_acc, stream=stream, events=ev_acc)
@@ -276,14 +284,25 @@ def main():
         for _ in range(n):
             graph.replay()
     t_graph = timed(lambda: replay_steps(args.steps), n=1) / args.steps
+    # the attention call alone with the K pool in the other page layout (slot-major rows / operand order)
+    k_other = att.k_cache
+    if not kop and cfg.dtype == "bf16":
+        from isd_inputs import k_pages_in_operand_order
+        k_other = k_pages_in_operand_order(att.k_cache)
+    t_att_kop, t_att_other = (timed(lambda: idlm.idlm_isd_attention(
+        att.q, kk, att.v_cache, att.block_table, att.ctx_lens, S, out, num_workgroups=args.workgroups, workspace=ws_att,
+        k_operand_order=flag), n=10) for kk, flag in ((k_gpu, kop), (k_other, (not kop) and cfg.dtype == "bf16")))
+    del k_other
     launch_modes = {"timed_region_ms": ms_per_step, "eager_ms": t_plain, "graph_replay_ms": t_graph}
+    k_layouts = {"attention_call_ms_as_timed": t_att_kop, "attention_call_ms_other_k_page_layout": t_att_other,
+                 "timed_layout": "operand order" if kop else "slot-major"}
 
     # the two small kernels between steps (scatter of the stride's K/V rows; trim-and-commit and next
     # stride), timed on the same workload outside the timed region above
     k_new = torch.randn(B, S, cfg.Hkv, cfg.D, device=dev).to(att.q.dtype)
     v_new = torch.randn(B, S, cfg.Hkv, cfg.D, device=dev).to(att.q.dtype)
-    t_append = timed(lambda: idlm.idlm_isd_kv_append(k_new, v_new, att.k_cache, att.v_cache, att.block_table,
-                                                     att.ctx_lens, S), n=20)
+    t_append = timed(lambda: idlm.idlm_isd_kv_append(k_new, v_new, k_gpu, att.v_cache, att.block_table,
+                                                     att.ctx_lens, S, k_operand_order=kop), n=20)
     pages_used = (att.ctx_lens + cfg.P - 1) // cfg.P
     n_steady = max(0, (S - 1) // 2)
 
@@ -409,7 +428,8 @@ def main():
                                "layer + one acceptance pass per step"
                                % (cfg.name, B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, V, cfg.ctx_kind, cfg.ctx_lo,
                                   cfg.ctx_hi, int(ctx_np.sum())),
-                   "attention_workgroups": nwg, "logits_dtype": "f32"},
+                   "attention_workgroups": nwg, "logits_dtype": "f32",
+                   "k_pages": "operand order" if kop else "slot-major"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
@@ -417,6 +437,7 @@ def main():
         "stream_ceiling": stream_probe,
         "between_steps": loop_kernels,
         "launch_modes": launch_modes,
+        "k_page_layouts": k_layouts,
         "accept_general": gen,
         "accept_bf16_logits": bf16_acc,
         "gated_lora_linear": lora,

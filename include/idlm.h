@@ -60,7 +60,14 @@ enum {
 
 enum {
     IDLM_DTYPE_F32 = 0,
-    IDLM_DTYPE_BF16 = 1
+    IDLM_DTYPE_BF16 = 1,
+    /* bf16 with the K pool's pages in operand order: inside the 4 KB block of a (page, KV head),
+     * the 16-byte chunk c (dims 8c .. 8c+7) of slot t is stored at 16-byte entry
+     * 64*(c/4) + 16*(c%4) + t instead of 16*t + c.  The attention kernel then reads K in whole
+     * cache lines (it matters when more than 64 query rows share a KV head, S*G > 64, and K/V are
+     * read by several wavefronts).  Needs token_stride = D = 128, P = 16; the V pool is unchanged.
+     * idlm_isd_kv_append writes this layout when given the same code. */
+    IDLM_DTYPE_BF16_KOP = 2
 };
 
 /*

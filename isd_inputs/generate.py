@@ -35,6 +35,16 @@ def to_numpy(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().contiguous().numpy()
 
 
+def k_pages_in_operand_order(k_cache: torch.Tensor) -> torch.Tensor:
+    """The K pool [num_pages, Hkv, 16, 128] (contiguous) with the 16-byte chunks of every (page, head)
+    block permuted from slot-major (entry 16*t + c) to the order the attention kernel's matrix operands
+    use (entry 64*(c/4) + 16*(c%4) + t).  A pure permutation of the stored bytes."""
+    pages, Hkv, P, D = k_cache.shape
+    assert P == 16 and D == 128 and k_cache.is_contiguous()
+    v = k_cache.view(pages, Hkv, 16, 4, 4, 8)              # [.., t, c/4, c%4, 8 elements]
+    return v.permute(0, 1, 3, 4, 2, 5).contiguous().view(pages, Hkv, P, D)
+
+
 def _torch_dtype(name: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
 

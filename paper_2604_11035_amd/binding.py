@@ -124,7 +124,7 @@ def _events_arg(events):
 
 
 def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, scale=0.0, num_workgroups=0,
-                       workspace=None, stream=None, events=None):
+                       workspace=None, stream=None, events=None, k_operand_order=False):
     """out[b,i,h,:] = causal attention of stride row i over the paged KV cache (see idlm.h).
 
     q, out: [B,S,Hq,D]; k_cache, v_cache: [num_pages,Hkv,P,D] (any strides with a contiguous
@@ -144,7 +144,8 @@ def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, sc
     rc = lib().idlm_isd_attention_ev(
         _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
         B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
-        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale), _dtype_code(q),
+        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale),
+        2 if k_operand_order else _dtype_code(q),
         int(num_workgroups), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
         _stream(stream), _events_arg(events))
     if rc != 0:
@@ -219,7 +220,8 @@ def idlm_stream_read(src, sink, stream=None):
         raise IdlmError(rc, "idlm_stream_read")
 
 
-def idlm_isd_kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S, *, stream=None):
+def idlm_isd_kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S, *, stream=None,
+                       k_operand_order=False):
     """Scatters the stride's K/V rows [B,S,Hkv,D] into the paged pools (see idlm.h)."""
     B, S_, Hkv, D = k_new.shape
     assert S_ == S and v_new.shape == k_new.shape and k_new.is_contiguous() and v_new.is_contiguous()
@@ -230,7 +232,8 @@ def idlm_isd_kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S,
     assert block_table.is_contiguous() and ctx_lens.is_contiguous() and block_table.shape[0] == B
     rc = lib().idlm_isd_kv_append(_ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache), _ptr(block_table),
                                   _ptr(ctx_lens), S, B, Hkv, D, P, num_pages, block_table.shape[1],
-                                  k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), _dtype_code(k_new),
+                                  k_cache.stride(0), k_cache.stride(1), k_cache.stride(2),
+                                  2 if k_operand_order else _dtype_code(k_new),
                                   _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_kv_append")

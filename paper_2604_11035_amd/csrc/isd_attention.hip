@@ -48,6 +48,7 @@ struct AttnParams {
                     //                   last): eight fp16 per entry, normalised per row to a largest magnitude of 1
     f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator l, largest magnitude of O / l, unused
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
+    int k_operand_order;   // K pages hold their 16-byte chunks in MFMA operand order (IDLM_DTYPE_BF16_KOP)
     int num_pages;
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
@@ -270,15 +271,18 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         u32x4 tv[8];       // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
         // Addresses are a wave-uniform 64-bit page base plus a 32-bit lane offset (the host checks that
         // the offset fits): one address register per lane instead of a 64-bit pair per page.
-        const uint32_t klane = (uint32_t)(n * (int)p.token_stride + g * 8);
+        // K pages in operand order: the 16 bytes that lane l needs for k-step s sit at entry 64*s + l of the
+        // page's 4 KB block, so a load instruction reads 1 KB of whole cache lines instead of 16 rows x 64 bytes
+        const uint32_t klane = p.k_operand_order ? (uint32_t)(lane * 8) : (uint32_t)(n * (int)p.token_stride + g * 8);
+        const int kstep = p.k_operand_order ? 512 : 32;
         const uint32_t vlane = (uint32_t)(4 * g * (int)p.token_stride + n * 8);
         auto load_k = [&](int pg0, int pg1) {
             const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride;
             const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k0 + klane + 32 * s)));
-                tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k1 + klane + 32 * s)));
+                tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k0 + klane + kstep * s)));
+                tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k1 + klane + kstep * s)));
             }
         };
         auto load_v = [&](int pg0, int pg1) {
@@ -727,12 +731,15 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
                       int32_t max_pages, int32_t dtype, int* err)
 {
     *err = IDLM_OK;
-    if (dtype != IDLM_DTYPE_F32 && dtype != IDLM_DTYPE_BF16) { *err = IDLM_ERR_DTYPE; return false; }
+    if (dtype != IDLM_DTYPE_F32 && dtype != IDLM_DTYPE_BF16 && dtype != IDLM_DTYPE_BF16_KOP) {
+        *err = IDLM_ERR_DTYPE;
+        return false;
+    }
     if (B < 0 || B > 65535 || S < 1 || S > 32 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || Hkv > 65535 ||
         P != 16 || max_pages < 1 || (int64_t)max_pages * P >= (1 << 30) ||
         (int64_t)B * max_pages >= (1LL << 31)) { *err = IDLM_ERR_SHAPE; return false; }
     const int G = Hq / Hkv;
-    if (dtype == IDLM_DTYPE_BF16) {
+    if (dtype != IDLM_DTYPE_F32) {
         if (D != 128) { *err = IDLM_ERR_DTYPE; return false; }
         if (S * G > 256) { *err = IDLM_ERR_SHAPE; return false; }
     } else {
@@ -761,7 +768,7 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
 {
     int err;
     if (!shapes_ok(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, &err)) return 0;
-    if (dtype != IDLM_DTYPE_BF16 || B == 0) return 0;
+    if (dtype == IDLM_DTYPE_F32 || B == 0) return 0;
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
     // two partial slots of 16*NB rows per wavefront of the largest grid
@@ -784,7 +791,8 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return IDLM_ERR_SHAPE;
     if (B == 0) return IDLM_OK;
     if (!q || !k_cache || !v_cache || !block_table || !ctx_lens || !out) return IDLM_ERR_NULL;
-    const size_t esz = dtype == IDLM_DTYPE_BF16 ? 2 : 4;
+    const size_t esz = dtype == IDLM_DTYPE_F32 ? 4 : 2;
+    if (dtype == IDLM_DTYPE_BF16_KOP && token_stride != D) return IDLM_ERR_DTYPE;   // a page's 4 KB per head must be one block
     if (!aligned(q, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(out, 16) ||
         !aligned(block_table, 4) || !aligned(ctx_lens, 4))
         return IDLM_ERR_ALIGN;
@@ -843,6 +851,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.out = static_cast<uint16_t*>(out);
     p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.M = S * G; p.max_pages = max_pages_per_seq;
     p.num_pages = num_pages;
+    p.k_operand_order = dtype == IDLM_DTYPE_BF16_KOP;
     int NB;
     row_tiling(p.M, &NB, &p.RG);
     p.Mpad = 16 * NB;

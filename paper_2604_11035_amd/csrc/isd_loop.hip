@@ -18,6 +18,7 @@ struct AppendParams {
     const int32_t* ctx_lens;
     int B, S, Hkv, P, num_pages, max_pages;
     int chunks;          // 16-byte chunks per row (D * element size / 16)
+    int k_operand_order; // K pages hold their 16-byte chunks in the attention kernel's operand order
     int64_t page_bytes, head_bytes, token_bytes;
 };
 
@@ -40,7 +41,11 @@ __global__ __launch_bounds__(256) void isd_kv_append_kernel(const AppendParams p
         if (t < 0 || t / p.P >= p.max_pages) continue;
         const int page = p.block_table[(int64_t)b * p.max_pages + t / p.P];
         if (page < 0 || page >= p.num_pages) continue;
-        const int64_t dst = page * p.page_bytes + h * p.head_bytes + (t % p.P) * p.token_bytes + (int64_t)c * 16;
+        int64_t dst = page * p.page_bytes + h * p.head_bytes;
+        if (p.k_operand_order && !is_v)   // chunk c of slot t%16 is entry 64*(c/4) + 16*(c%4) + slot of the 4 KB block
+            dst += (int64_t)(64 * (c >> 2) + 16 * (c & 3) + (int)(t % p.P)) * 16;
+        else
+            dst += (t % p.P) * p.token_bytes + (int64_t)c * 16;
         const int64_t src = (row * p.chunks + c) * 16;
         const u32x4 val = *reinterpret_cast<const u32x4*>((is_v ? p.v_new : p.k_new) + src);
         *reinterpret_cast<u32x4*>((is_v ? p.v_cache : p.k_cache) + dst) = val;
@@ -150,9 +155,10 @@ extern "C" int idlm_isd_kv_append(const void* k_new, const void* v_new, void* k_
                                   int64_t page_stride, int64_t head_stride, int64_t token_stride, int32_t dtype,
                                   void* stream)
 {
-    if (dtype != IDLM_DTYPE_F32 && dtype != IDLM_DTYPE_BF16) return IDLM_ERR_DTYPE;
+    if (dtype != IDLM_DTYPE_F32 && dtype != IDLM_DTYPE_BF16 && dtype != IDLM_DTYPE_BF16_KOP) return IDLM_ERR_DTYPE;
     if (B < 0 || B > 65535 || S < 1 || S > 64 || Hkv < 1 || Hkv > 1024 || D < 1 || D > 1024 || P < 1 || P > 1024)
         return IDLM_ERR_SHAPE;
+    if (dtype == IDLM_DTYPE_BF16_KOP && (D != 128 || P != 16 || token_stride != 128)) return IDLM_ERR_DTYPE;
     if (num_pages < 1 || max_pages_per_seq < 1 || page_stride < 1 || head_stride < 1 || token_stride < D)
         return IDLM_ERR_SHAPE;
     if (B == 0) return IDLM_OK;
@@ -172,6 +178,7 @@ extern "C" int idlm_isd_kv_append(const void* k_new, const void* v_new, void* k_
     p.ctx_lens = ctx_lens;
     p.B = B; p.S = S; p.Hkv = Hkv; p.P = P; p.num_pages = num_pages; p.max_pages = max_pages_per_seq;
     p.chunks = (int)(D * esz / 16);
+    p.k_operand_order = dtype == IDLM_DTYPE_BF16_KOP;
     p.page_bytes = page_stride * esz; p.head_bytes = head_stride * esz; p.token_bytes = token_stride * esz;
     const int64_t threads = (int64_t)2 * B * S * Hkv * p.chunks;
     int64_t blocks = (threads + 255) / 256;

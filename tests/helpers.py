@@ -20,8 +20,9 @@ def bf16_to_f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def gpu_attention(inp, num_workgroups=0, scale=0.0):
-    """Runs idlm_isd_attention on `inp` (tensors must live on the GPU); returns float64 numpy."""
+def gpu_attention(inp, num_workgroups=0, scale=0.0, k_operand_order=False):
+    """Runs idlm_isd_attention on `inp` (tensors must live on the GPU); returns float64 numpy.
+    k_operand_order: hand the K pool over in the kernel's operand-order page layout (a permuted copy)."""
     cfg = inp.cfg
     out = torch.full_like(inp.q, float("nan"))
     dcode = 1 if inp.q.dtype == torch.bfloat16 else 0
@@ -29,8 +30,12 @@ def gpu_attention(inp, num_workgroups=0, scale=0.0):
     Hkv, P = inp.k_cache.shape[1], inp.k_cache.shape[2]
     nbytes = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, inp.block_table.shape[1], dcode)
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=inp.q.device)
-    idlm.idlm_isd_attention(inp.q, inp.k_cache, inp.v_cache, inp.block_table, inp.ctx_lens, S, out,
-                            scale=scale, num_workgroups=num_workgroups, workspace=ws)
+    k_cache = inp.k_cache
+    if k_operand_order:
+        from isd_inputs import k_pages_in_operand_order
+        k_cache = k_pages_in_operand_order(inp.k_cache)
+    idlm.idlm_isd_attention(inp.q, k_cache, inp.v_cache, inp.block_table, inp.ctx_lens, S, out,
+                            scale=scale, num_workgroups=num_workgroups, workspace=ws, k_operand_order=k_operand_order)
     torch.cuda.synchronize()
     return bf16_to_f64(out)
 

@@ -44,6 +44,7 @@ def test_workspace_sizes_are_host_only_and_monotone():
     assert idlm.idlm_isd_accept_workspace(4, 65, 1024) == 0
     w = idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 1)
     assert w > 0
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 2) == w   # operand-order K pages: same kernels
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 0) == 0   # fp32 path needs none
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64 unsupported
     assert idlm.idlm_isd_attention_workspace(256, 33, 32, 8, 128, 16, 512, 1) == 0
@@ -70,8 +71,10 @@ def _attention(**kw):
     (dict(S=32, Hq=32, Hkv=2), -2),            # S*G = 512 rows
     (dict(nwg=-1), -2), (dict(nwg=5000), -2), (dict(ts=64), -2),
     (dict(dtype=7), -3), (dict(D=64), -3), (dict(D=96, dtype=0), -3),
+    (dict(dtype=2, D=64), -3), (dict(dtype=2, ts=256, hs=128, ps=16 * 256), -3),   # operand-order K pages need D = token_stride = 128
     (dict(q=ODD), -4), (dict(k=ODD), -4), (dict(ts=132), -4),
     (dict(), -5),                              # bf16 path without a workspace
+    (dict(dtype=2), -5),                       # operand-order K pages: the same path
     (dict(ws=FAKE, ws_bytes=16), -5),
 ])
 def test_attention_rejects_bad_arguments(kw, code):
@@ -138,7 +141,7 @@ def _append(**kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(kn=None), -1), (dict(vc=None), -1), (dict(ctx=None), -1),
     (dict(S=0), -2), (dict(S=65), -2), (dict(B=70000), -2), (dict(num_pages=0), -2), (dict(ts=64), -2),
-    (dict(dtype=5), -3),
+    (dict(dtype=5), -3), (dict(dtype=2, D=64, ts=64), -3), (dict(dtype=2, ts=256), -3), (dict(dtype=2, P=32), -3),
     (dict(kn=ODD), -4), (dict(kc=ODD), -4), (dict(D=4), -4), (dict(ts=132), -4),
 ])
 def test_kv_append_rejects_bad_arguments(kw, code):

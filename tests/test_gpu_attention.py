@@ -24,6 +24,10 @@ def _check(inp, num_workgroups=0, sel=None, scale=0.0, tol=None):
     assert nvec > 0
     assert rel <= tol, "max relative error %g over %d vectors" % (rel, nvec)
     print("max relative error %.3g over %d vectors" % (rel, nvec))
+    if inp.q.dtype == torch.bfloat16 and inp.k_cache.is_contiguous():
+        # the same K pool with its pages in operand order: other addresses, the same arithmetic, the same bits
+        alt = h.gpu_attention(inp, num_workgroups=num_workgroups, scale=scale, k_operand_order=True)
+        assert np.array_equal(alt, got), "the operand-order K layout changed the result"
     return got, ref
 
 

@@ -59,6 +59,38 @@ def test_kv_append_matches_the_oracle_bit_for_bit(dtype, B, S, Hkv, D):
     assert np.array_equal(back(g_vc).view(np.uint32 if dtype == "f32" else np.uint16), vc.view(np.uint32 if dtype == "f32" else np.uint16))
 
 
+def test_kv_append_writes_k_pages_in_operand_order():
+    """The K pool laid out for the attention kernel's operands: what the kernel writes equals the oracle's
+    row-major pool put through the permutation; V is untouched by the option."""
+    from isd_inputs import k_pages_in_operand_order
+    B, S, Hkv, D, P = 9, 5, 4, 128, 16
+    rng = np.random.default_rng(3)
+    ctx = (rng.integers(1, 70, size=B) + S).astype(np.int32)
+    max_pages = int((ctx.max() + P - 1) // P)
+    pages = (ctx + P - 1) // P
+    num_pages = int(pages.sum()) + 3
+    perm = rng.permutation(num_pages).astype(np.int32)
+    table = np.full((B, max_pages), -1, np.int32)
+    k = 0
+    for b in range(B):
+        table[b, :pages[b]] = perm[k:k + pages[b]]; k += pages[b]
+    kc = torch.randn(num_pages, Hkv, P, D, device=DEV).to(torch.bfloat16)
+    vc = torch.randn(num_pages, Hkv, P, D, device=DEV).to(torch.bfloat16)
+    kn = torch.randn(B, S, Hkv, D, device=DEV).to(torch.bfloat16)
+    vn = torch.randn(B, S, Hkv, D, device=DEV).to(torch.bfloat16)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    o_k, o_v = bits(kc).copy(), bits(vc).copy()
+    oracle.kv_append(bits(kn), bits(vn), o_k, o_v, table, ctx, S, Hkv=Hkv, D=D, P=P)
+    g_k = k_pages_in_operand_order(kc)           # the pool as the option keeps it
+    g_v = vc.clone()
+    idlm.idlm_isd_kv_append(kn, vn, g_k, g_v, torch.from_numpy(table).to(DEV), torch.from_numpy(ctx).to(DEV), S,
+                            k_operand_order=True)
+    torch.cuda.synchronize()
+    want_k = k_pages_in_operand_order(torch.from_numpy(o_k.view(np.int16)).view(torch.bfloat16).view(num_pages, Hkv, P, D).to(DEV))
+    assert torch.equal(g_k.view(torch.int16), want_k.view(torch.int16))
+    assert np.array_equal(bits(g_v), o_v)
+
+
 def test_kv_append_into_a_token_major_pool():
     rng = np.random.default_rng(9)
     B, S, Hkv, D, P = 6, 8, 4, 128, 16
