@@ -205,11 +205,14 @@ def test_commit_refusals_change_nothing():
 
 # ---- the whole loop --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("N,greedy", [(3, False), (4, True)])
-def test_several_steps_of_the_whole_loop(N, greedy):
+@pytest.mark.parametrize("N,greedy,kop", [(3, False, False), (4, True, False), (3, True, True)])
+def test_several_steps_of_the_whole_loop(N, greedy, kop):
     """append -> attention -> accept -> commit, eight steps, state compared after every call.
     There is no model here: K/V rows and Q are seeded noise, logits are seeded noise with a planted
-    peak on every draft (so that some drafts pass and some do not)."""
+    peak on every draft (so that some drafts pass and some do not).  kop: the K pool lives in the
+    attention kernel's operand order from the start (the oracle's pool stays slot-major; the two
+    are compared through the permutation)."""
+    from isd_inputs import k_pages_in_operand_order
     rng = np.random.default_rng(40 + N)
     B, S, Hq, Hkv, D, P, V = 24, 2 * N - 1, 16, 4, 128, 16, 4096
     steps, max_pages = 8, 16
@@ -234,18 +237,21 @@ def test_several_steps_of_the_whole_loop(N, greedy):
     kc = bf(rng.standard_normal((num_pages, Hkv, P, D)).astype(np.float32))    # prompts' K/V: anything
     vc = bf(rng.standard_normal((num_pages, Hkv, P, D)).astype(np.float32))
     o_kc, o_vc = bits(kc).copy(), bits(vc).copy()
+    if kop:
+        kc = k_pages_in_operand_order(kc)
+    as_stored = lambda o: bits(k_pages_in_operand_order(torch.from_numpy(o.view(np.int16)).view(torch.bfloat16).to(DEV))) if kop else o
     gflag = np.full(B, 1 if greedy else 0, np.uint8)
     ws_a = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages, 1)), dtype=torch.uint8, device=DEV)
     ws_c = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=DEV)
     finalised = 0
     for step in range(steps):
         kn, vn, q = (bf(rng.standard_normal(shape).astype(np.float32)) for shape in ((B, S, Hkv, D), (B, S, Hkv, D), (B, S, Hq, D)))
-        idlm.idlm_isd_kv_append(kn, vn, kc, vc, g["block_table"], g["ctx_lens"], S)
+        idlm.idlm_isd_kv_append(kn, vn, kc, vc, g["block_table"], g["ctx_lens"], S, k_operand_order=kop)
         oracle.kv_append(bits(kn), bits(vn), o_kc, o_vc, st["block_table"], st["ctx_lens"], S, Hkv=Hkv, D=D, P=P)
         out = torch.empty_like(q)
-        idlm.idlm_isd_attention(q, kc, vc, g["block_table"], g["ctx_lens"], S, out, workspace=ws_a)
+        idlm.idlm_isd_attention(q, kc, vc, g["block_table"], g["ctx_lens"], S, out, workspace=ws_a, k_operand_order=kop)
         torch.cuda.synchronize()
-        assert np.array_equal(bits(kc), o_kc) and np.array_equal(bits(vc), o_vc)
+        assert np.array_equal(bits(kc), as_stored(o_kc)) and np.array_equal(bits(vc), o_vc)
         ref = oracle.attention(bits(q), o_kc, o_vc, st["block_table"], st["ctx_lens"], S, Hq=Hq, Hkv=Hkv, D=D, P=P)
         err, _ = attention_errors(out.float().cpu().numpy().astype(np.float64), ref)
         assert err <= ATTN_REL_TOL
