@@ -14,18 +14,31 @@ namespace idlm {
 struct ChainResult {   // what the sampling pass needs to know about a sequence
     int row;           // stride row r that emits the fresh token, or -1 (greedy: nothing to sample)
     int excluded;      // token id removed from the sample (the rejected draft), or -1
-    float skip_below;  // logits below this cannot win the Gumbel-max of row r (-inf: no such bound)
+    float floor;       // a score that the winner of row r's Gumbel-max reaches or exceeds (-inf: none known)
     int pad;
 };
 
-// The Gumbel noise of a 24-bit uniform lies in [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355].
-// If some element j that takes part in the sample has l_j = c, the winner scores at least c - 2.8115, so
-// an element with l_i < c - 19.5 has l_i + g_i < c - 19.5 + 16.6355 < l_j + g_j whatever the noise: it
-// is skipped without evaluating its noise, and the arg-max is exactly that of the full evaluation
-// (0.05 of slack covers the rounding of the noise and of the sums).  c is the row maximum, or, when the
-// arg-max itself is the excluded token (the usual rejection), the value of another element that the
-// row-statistics pass brings along (RowPartial::m2).
+// Pruning of the Gumbel-max, exact.  Let c be a score that the winner is known to reach (a "floor").
+// Element i wins only if l_i + g_i > c, i.e. -ln u_i < e^(l_i - c), which needs 1 - u_i < e^(l_i - c)
+// (because e^-x >= 1 - x).  1 - u_i is exact for the 24-bit uniform, so an element whose 1 - u_i is not
+// below e^(l_i - c) (taken 0.7 % larger: covers the rounding of the exponential, of the noise and of the
+// sums) is dropped before its two logarithms; on average only e^(LSE - c) = O(1) elements of a row
+// survive.  Before even drawing the Philox block of four elements: the noise lies in
+// [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355], so four logits all more than 19.5 below the
+// floor cannot win whatever their uniforms are.
+// The floor starts as the score of the row's arg-max element (computed by the chain kernel with the same
+// arithmetic), or, when the arg-max is the excluded token (the usual rejection), as m2 - 2.82 with m2 the
+// value of another element that the row-statistics pass brings along (RowPartial::m2), and rises with the
+// thread's own best.  Every dropped element would have failed the comparison it skips, so the sequence
+// of updates, and with it the result, is that of the full evaluation.
 constexpr float kGumbelSpan = 19.5f;
+constexpr float kGumbelMin = -2.82f;
+
+// 1 - u for u = (2*(x >> 9) + 1) * 2^-24: again an odd 24-bit numerator, exact in fp32
+__device__ __forceinline__ float one_minus_uniform(uint32_t x)
+{
+    return (float)(2u * (0x7FFFFFu - (x >> 9)) + 1u) * 5.9604644775390625e-8f;
+}
 
 struct AcceptWorkspace {
     size_t stats_off, keys_off, chain_off, total;
@@ -109,7 +122,16 @@ __global__ __launch_bounds__(64) void isd_accept_chain_kernel(
         ChainResult cr;
         cr.row = is_greedy ? -1 : r;
         cr.excluded = (r < n_d) ? x_r : -1;
-        cr.skip_below = ((cr.excluded == a_r) ? m2_r : m_r) - kGumbelSpan;
+        cr.floor = -INFINITY;
+        if (!is_greedy && m_r > -INFINITY) {
+            if (cr.excluded == a_r) {
+                cr.floor = m2_r + kGumbelMin;
+            } else {   // the arg-max element's own score, as the sampling pass will compute it
+                const uint4 w = philox4x32_10(make_uint4((uint32_t)(a_r >> 2), (uint32_t)(b * S + r), 1u, rng_offset), key);
+                const int k = a_r & 3;
+                cr.floor = m_r + gumbel(k == 0 ? w.x : k == 1 ? w.y : k == 2 ? w.z : w.w);
+            }
+        }
         cr.pad = 0;
         chain[b] = cr;
         keys[b] = 0ull;   // "nothing sampled yet"
@@ -144,7 +166,15 @@ __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
     const int fend = min(V, (c + 1) * gchunk) / N;
     float best = -INFINITY;
     int bidx = INT_MAX;
-    const float skip_below = cr.skip_below;
+    const float floor0 = cr.floor;
+    float thr = floor0;   // max(floor, this thread's best so far)
+    auto may_win = [&](float l, uint32_t word) {
+        return one_minus_uniform(word) < fast_exp2(fmaf(l - thr, kLog2e, 0.01f));
+    };
+    auto evaluate = [&](float l, uint32_t word, int idx) {
+        const float s = l + gumbel(word);
+        if (idx != excluded && s > best) { best = s; bidx = idx; }
+    };
     for (int f0 = fbeg + tid; f0 < fend; f0 += 4 * 256) {   // four loads in flight, then the noise of what can win
         raw_t v[4];
 #pragma unroll
@@ -160,15 +190,20 @@ __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
             LV::unpack(v[u], e);
 #pragma unroll
             for (int h = 0; h < N / 4; ++h) {   // one Philox block per four consecutive elements
-                if (fmaxf(fmaxf(e[h * 4], e[h * 4 + 1]), fmaxf(e[h * 4 + 2], e[h * 4 + 3])) < skip_below) continue;
+                if (fmaxf(fmaxf(e[h * 4], e[h * 4 + 1]), fmaxf(e[h * 4 + 2], e[h * 4 + 3])) < thr - kGumbelSpan) continue;
                 const int i0 = f * N + h * 4;
                 const uint4 w = philox4x32_10(make_uint4((uint32_t)(i0 >> 2), row, 1u, rng_offset), key);
-                const float s0 = e[h * 4] + gumbel(w.x), s1 = e[h * 4 + 1] + gumbel(w.y);
-                const float s2 = e[h * 4 + 2] + gumbel(w.z), s3 = e[h * 4 + 3] + gumbel(w.w);
-                if (i0 != excluded && s0 > best) { best = s0; bidx = i0; }
-                if (i0 + 1 != excluded && s1 > best) { best = s1; bidx = i0 + 1; }
-                if (i0 + 2 != excluded && s2 > best) { best = s2; bidx = i0 + 2; }
-                if (i0 + 3 != excluded && s3 > best) { best = s3; bidx = i0 + 3; }
+                const bool p0 = may_win(e[h * 4], w.x), p1 = may_win(e[h * 4 + 1], w.y);
+                const bool p2 = may_win(e[h * 4 + 2], w.z), p3 = may_win(e[h * 4 + 3], w.w);
+                // a branch of the whole wavefront (rarely taken), so that the logarithms are not computed
+                // speculatively for everything
+                if (__ballot(p0 || p1 || p2 || p3) != 0ull) {
+                    if (p0) evaluate(e[h * 4], w.x, i0);
+                    if (p1) evaluate(e[h * 4 + 1], w.y, i0 + 1);
+                    if (p2) evaluate(e[h * 4 + 2], w.z, i0 + 2);
+                    if (p3) evaluate(e[h * 4 + 3], w.w, i0 + 3);
+                    thr = fmaxf(best, floor0);
+                }
             }
         }
     }
