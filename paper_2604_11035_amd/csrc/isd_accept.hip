@@ -24,14 +24,14 @@ struct ChainResult {   // what the sampling pass needs to know about a sequence
 // below e^(l_i - c) (taken 0.7 % larger: covers the rounding of the exponential, of the noise and of the
 // sums) is dropped before its two logarithms; on average only e^(LSE - c) = O(1) elements of a row
 // survive.  Before even drawing the Philox block of four elements: the noise lies in
-// [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355], so four logits all more than 19.5 below the
-// floor cannot win whatever their uniforms are.
+// [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355], so four logits all more than 16.7 below the
+// floor (a score) cannot win whatever their uniforms are.
 // The floor starts as the score of the row's arg-max element (computed by the chain kernel with the same
 // arithmetic), or, when the arg-max is the excluded token (the usual rejection), as m2 - 2.82 with m2 the
 // value of another element that the row-statistics pass brings along (RowPartial::m2), and rises with the
 // thread's own best.  Every dropped element would have failed the comparison it skips, so the sequence
 // of updates, and with it the result, is that of the full evaluation.
-constexpr float kGumbelSpan = 19.5f;
+constexpr float kNoiseMax = 16.7f;
 constexpr float kGumbelMin = -2.82f;
 
 // 1 - u for u = (2*(x >> 9) + 1) * 2^-24: again an odd 24-bit numerator, exact in fp32
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void isd_accept_sample_kernel(
             LV::unpack(v[u], e);
 #pragma unroll
             for (int h = 0; h < N / 4; ++h) {   // one Philox block per four consecutive elements
-                if (fmaxf(fmaxf(e[h * 4], e[h * 4 + 1]), fmaxf(e[h * 4 + 2], e[h * 4 + 3])) < thr - kGumbelSpan) continue;
+                if (fmaxf(fmaxf(e[h * 4], e[h * 4 + 1]), fmaxf(e[h * 4 + 2], e[h * 4 + 3])) < thr - kNoiseMax) continue;
                 const int i0 = f * N + h * 4;
                 const uint4 w = philox4x32_10(make_uint4((uint32_t)(i0 >> 2), row, 1u, rng_offset), key);
                 const bool p0 = may_win(e[h * 4], w.x), p1 = may_win(e[h * 4 + 1], w.y);
