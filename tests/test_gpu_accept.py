@@ -139,3 +139,22 @@ def test_empty_batch_is_a_noop():
     nt = torch.empty(0, 4, dtype=torch.int32, device=DEV)
     idlm.idlm_isd_accept(logits, torch.empty(0, 3, dtype=torch.int32, device=DEV), 1, al, nt, n_draft=1)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("S,V,B", [(64, 1024, 5), (64, 50000, 3), (33, 151936, 4)])
+def test_largest_strides(S, V, B):
+    """S = 64 is the most rows a sequence may have (one lane of the chain's wavefront per row); every
+    draft count from 0 to S-1 occurs, greedy and stochastic."""
+    h = _helpers()
+    rng = np.random.default_rng(S + V)
+    logits = (rng.standard_normal((B, S, V)) * 2).astype(np.float32)
+    drafts = logits.argmax(-1)[:, :S - 1]
+    flip = rng.random(drafts.shape) < 0.05
+    drafts = np.where(flip, rng.integers(0, V, drafts.shape), drafts)
+    logits[np.arange(B)[:, None], np.arange(S - 1)[None, :], logits.argmax(-1)[:, :S - 1]] += 6.0   # confident rows: long accepted prefixes
+    nd = np.array([S - 1, 0, S // 2, 1, S - 2][:B])
+    gr = np.array([1, 0, 0, 1, 0][:B])
+    inp = _custom(logits, drafts, nd, gr, seed=77)
+    got, ref = h.gpu_accept(inp), h.oracle_accept(inp)
+    h.compare_accept(got, ref, nd, strict=False)
+    assert ref["accept_len"].max() >= 8
