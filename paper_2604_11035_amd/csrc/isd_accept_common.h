@@ -232,6 +232,28 @@ __device__ __forceinline__ float gumbel(uint32_t x)
     return -0.69314718056f * __builtin_amdgcn_logf(t);
 }
 
+// Pruning of the Gumbel-max, exact.  Let c be a score that the winner is known to reach (a "floor").
+// Element i wins only if l_i + g_i > c, i.e. -ln u_i < e^(l_i - c), which needs 1 - u_i < e^(l_i - c)
+// (because e^-x >= 1 - x).  1 - u_i is exact for the 24-bit uniform, so an element whose 1 - u_i is not
+// below e^(l_i - c) (taken 0.7 % larger: covers the rounding of the exponential, of the noise and of the
+// sums) is dropped before its two logarithms; on average only e^(LSE - c) = O(1) elements of a row
+// survive.  Before even drawing the Philox block of four elements: the noise lies in
+// [-ln(-ln 2^-24), -ln(-ln(1 - 2^-24))] = [-2.8115, 16.6355], so four logits all more than 16.7 below the
+// floor (a score) cannot win whatever their uniforms are.
+// The floor starts as the score of the row's arg-max element (computed by the chain kernel with the same
+// arithmetic), or, when the arg-max is the excluded token (the usual rejection), as m2 - 2.82 with m2 the
+// value of another element that the row-statistics pass brings along (RowPartial::m2), and rises with the
+// thread's own best.  Every dropped element would have failed the comparison it skips, so the sequence
+// of updates, and with it the result, is that of the full evaluation.
+constexpr float kNoiseMax = 16.7f;
+constexpr float kGumbelMin = -2.82f;
+
+// 1 - u for u = (2*(x >> 9) + 1) * 2^-24: again an odd 24-bit numerator, exact in fp32
+__device__ __forceinline__ float one_minus_uniform(uint32_t x)
+{
+    return (float)(2u * (0x7FFFFFu - (x >> 9)) + 1u) * 5.9604644775390625e-8f;
+}
+
 // ---- launch shapes shared by the acceptance entry points (host) ---------------------------------
 
 struct AcceptPlan {

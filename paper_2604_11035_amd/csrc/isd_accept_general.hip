@@ -27,7 +27,7 @@ struct SampleJob {     // one row that needs a Gumbel-max pass
     float lse2;        // log2 sum 2^(l*k) of the row
     int q_row;         // JOB_RESID_Q: row of q_logits (inside the sequence)
     float q_lse2;      // ... and its log2-sum
-    int pad;
+    float floor;       // JOB_PLAIN / JOB_RESID_POINT: a score the winner reaches or exceeds (-inf: none known)
 };
 
 struct GeneralParams {
@@ -55,10 +55,14 @@ struct GeneralParams {
     float one_plus_tau;
 };
 
-__device__ __forceinline__ void merged_stats(const RowPartial* sp, int nsplit, float k, float& m, float& z, int& a)
+__device__ __forceinline__ void merged_stats(const RowPartial* sp, int nsplit, float k, float& m, float& z, int& a,
+                                             float& m2)
 {
-    m = sp[0].m; z = sp[0].z; a = sp[0].arg;
-    for (int q = 1; q < nsplit; ++q) combine_stats(m, z, a, sp[q].m, sp[q].z, sp[q].arg, k);
+    m = sp[0].m; z = sp[0].z; a = sp[0].arg; m2 = sp[0].m2;
+    for (int q = 1; q < nsplit; ++q) {
+        m2 = combine_second(m, m2, sp[q].m, sp[q].m2);
+        combine_stats(m, z, a, sp[q].m, sp[q].z, sp[q].arg, k);
+    }
 }
 
 __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const GeneralParams p)
@@ -74,11 +78,11 @@ __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const Gene
     qr0 = max(0, min(qr0, S - n_d));          // the q rows of the drafts stay inside the sequence
 
     int a = 0, ok = 1, x = -1, my_qrow = 0;
-    float pr = 0.f, qv = 0.f, lse2 = 0.f, q_lse2 = 0.f;
+    float pr = 0.f, qv = 0.f, lse2 = 0.f, q_lse2 = 0.f, m = -INFINITY, m2 = -INFINITY;
     if (tid < S) {
         const int row = b * S + tid;
-        float m, z;
-        merged_stats(p.stats + (size_t)row * p.nsplit, p.nsplit, p.k, m, z, a);
+        float z;
+        merged_stats(p.stats + (size_t)row * p.nsplit, p.nsplit, p.k, m, z, a, m2);
         lse2 = ref_k(m, p.k) + __builtin_amdgcn_logf(z);       // log2 of the row's sum of 2^(l*k)
         if (p.row_lse) p.row_lse[row] = lse2 * kLn2;
         if (tid < n_d) {
@@ -92,9 +96,9 @@ __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const Gene
                 if (p.q_lse) {
                     q_lse2 = p.q_lse[qrow] * kLog2e;
                 } else {
-                    float mq, zq;
+                    float mq, zq, m2q;
                     int aq;
-                    merged_stats(p.q_stats + (size_t)qrow * p.nsplit, p.nsplit, p.k, mq, zq, aq);
+                    merged_stats(p.q_stats + (size_t)qrow * p.nsplit, p.nsplit, p.k, mq, zq, aq, m2q);
                     q_lse2 = ref_k(mq, p.k) + __builtin_amdgcn_logf(zq);
                 }
                 qv = valid ? fast_exp2(fmaf(p.q_logits[(size_t)qrow * V + x], p.k, -q_lse2)) : 0.f;
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const Gene
     if (tid < S) {
         SampleJob job;
         job.mode = JOB_NONE; job.stream = 1; job.excluded = -1; job.fallback = a; job.lse2 = lse2;
-        job.q_row = my_qrow; job.q_lse2 = q_lse2; job.pad = 0;
+        job.q_row = my_qrow; job.q_lse2 = q_lse2; job.floor = -INFINITY;
         int tok;
         if (tid < r) tok = x;
         else if (tid == r) {
@@ -136,6 +140,18 @@ __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const Gene
             if (p.sample_proposals && !is_greedy) { job.mode = JOB_PLAIN; job.stream = 2; }
         }
         const int row = b * S + tid;
+        if ((job.mode == JOB_PLAIN || job.mode == JOB_RESID_POINT) && m > -INFINITY) {
+            // floor of the Gumbel-max over l/T + g: the arg-max element's own score, or, when that element is
+            // the excluded one, the second-largest bound with the smallest possible noise
+            if (job.excluded == a) {
+                job.floor = m2 * p.inv_t + kGumbelMin;
+            } else {
+                const uint4 w = philox4x32_10(make_uint4((uint32_t)(a >> 2), (uint32_t)row, (uint32_t)job.stream, p.rng_offset),
+                                              p.key);
+                const int k4 = a & 3;
+                job.floor = m * p.inv_t + gumbel(k4 == 0 ? w.x : k4 == 1 ? w.y : k4 == 2 ? w.z : w.w);
+            }
+        }
         p.jobs[row] = job;
         p.keys[row] = 0ull;
         if (job.mode == JOB_NONE) p.new_tokens[row] = tok;
@@ -162,31 +178,51 @@ __global__ __launch_bounds__(256) void isd_accept_general_sample_kernel(const Ge
     const int fend = min(V, (c + 1) * gchunk) >> 2;
     float best = -INFINITY;
     int bidx = INT_MAX;
-    for (int f = fbeg + tid; f < fend; f += 256) {
-        const float4 v = l4[f];
-        const uint4 w = philox4x32_10(make_uint4((uint32_t)f, (uint32_t)row, (uint32_t)job.stream, p.rng_offset), p.key);
-        const float lv[4] = {v.x, v.y, v.z, v.w};
-        const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
-        float qv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (job.mode == JOB_RESID_Q) {
+    if (job.mode == JOB_RESID_Q) {
+        for (int f = fbeg + tid; f < fend; f += 256) {
+            const float4 v = l4[f];
             const float4 t = q4[f];
-            qv[0] = t.x; qv[1] = t.y; qv[2] = t.z; qv[3] = t.w;
-        }
+            const uint4 w = philox4x32_10(make_uint4((uint32_t)f, (uint32_t)row, (uint32_t)job.stream, p.rng_offset), p.key);
+            const float lv[4] = {v.x, v.y, v.z, v.w};
+            const float qv[4] = {t.x, t.y, t.z, t.w};
+            const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = f * 4 + e;
-            float s;
-            if (job.mode == JOB_RESID_Q) {
+            for (int e = 0; e < 4; ++e) {
                 // ln(p_i - q_i) + g_i over the elements where the anchor exceeds the proposal
                 const float pi = fast_exp2(fmaf(lv[e], p.k, -job.lse2));
                 const float qi = fast_exp2(fmaf(qv[e], p.k, -job.q_lse2));
                 if (!(pi > qi)) continue;
-                s = logf(pi - qi) + gumbel(wv[e]);
-            } else {
-                if (i == job.excluded) continue;
-                s = lv[e] * p.inv_t + gumbel(wv[e]);
+                const float s = logf(pi - qi) + gumbel(wv[e]);
+                if (s > best) { best = s; bidx = f * 4 + e; }
             }
-            if (s > best) { best = s; bidx = i; }
+        }
+    } else {
+        // l/T + g with the exact pruning of the Gumbel-max (see isd_accept_common.h): an element is evaluated
+        // only if 1 - u < e^(l/T - floor), behind a branch of the whole wavefront
+        const float floor0 = job.floor;
+        float thr = floor0;
+        auto may_win = [&](float l, uint32_t word) {
+            return one_minus_uniform(word) < fast_exp2(fmaf(l, p.k, fmaf(-thr, kLog2e, 0.01f)));
+        };
+        for (int f = fbeg + tid; f < fend; f += 256) {
+            const float4 v = l4[f];
+            if (fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)) * p.inv_t < thr - kNoiseMax) continue;
+            const uint4 w = philox4x32_10(make_uint4((uint32_t)f, (uint32_t)row, (uint32_t)job.stream, p.rng_offset), p.key);
+            const float lv[4] = {v.x, v.y, v.z, v.w};
+            const uint32_t wv[4] = {w.x, w.y, w.z, w.w};
+            bool pass[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pass[e] = may_win(lv[e], wv[e]);
+            if (__ballot(pass[0] || pass[1] || pass[2] || pass[3]) != 0ull) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = f * 4 + e;
+                    if (!pass[e] || i == job.excluded) continue;
+                    const float s = lv[e] * p.inv_t + gumbel(wv[e]);
+                    if (s > best) { best = s; bidx = i; }
+                }
+                thr = fmaxf(best, floor0);
+            }
         }
     }
 #pragma unroll
