@@ -92,15 +92,17 @@ enum {
  * block_table int32 [B,max_pages_per_seq].
  * ctx_lens    int32 [B]: KV length of each sequence INCLUDING this step's S rows.
  * scale       softmax scale; <= 0 selects 1/sqrt(D).
- * dtype       IDLM_DTYPE_BF16 (MFMA path; fp32 accumulation; D = 128; G = Hq/Hkv and S with
- *             S*G <= 256) or IDLM_DTYPE_F32 (plain fp32 path; D in {64,128}).
+ * dtype       IDLM_DTYPE_BF16 / IDLM_DTYPE_BF16_KOP at D = 128 (MFMA path; fp32 accumulation; G = Hq/Hkv
+ *             and S with S*G <= 256), or the plain path, one wavefront per (row, head) with fp32
+ *             arithmetic, for correctness rather than speed: IDLM_DTYPE_F32 with D in {64,128} and
+ *             IDLM_DTYPE_BF16 with D = 64.
  * num_workgroups  size of the persistent grid that shares the batch's 32-token tiles evenly;
  *             0 = one workgroup per compute unit of the current device, fewer when B and the
  *             width of the block table bound the work to a few tiles per wavefront (the setting to use);
  *             1..1024 forces a grid (testing, or leaving compute units to other streams).
- * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned (bf16 path:
+ * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned (MFMA path:
  *             partial results of the sequences that a slice boundary cuts;
- *             the fp32 path needs none and accepts NULL).
+ *             the plain path needs none and accepts NULL).
  * Supported: P = 16, 1 <= S <= 32, 0 <= B <= 65535 (B = 0 is a no-op), B*max_pages_per_seq < 2^31.
  */
 int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,

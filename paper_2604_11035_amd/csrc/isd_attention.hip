@@ -651,20 +651,33 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     }
 }
 
-// ---- fp32 path (small correctness configurations): one wavefront per (sequence, row, head) ----
+// ---- plain path (fp32, and bf16 at D = 64; small correctness configurations): one wavefront per
+// (sequence, row, head), fp32 arithmetic ----
 struct AttnParamsF32 {
-    const float* q;
-    const float* k;
-    const float* v;
+    const void* q;
+    const void* k;
+    const void* v;
     const int32_t* table;
     const int32_t* ctx;
-    float* out;
+    void* out;
     int S, Hq, Hkv, G, P, max_pages, num_pages;
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
 };
 
-template <int D>
+// four consecutive elements of a row as fp32 (bf16 widens exactly)
+template <bool BF16>
+__device__ __forceinline__ float4 load4(const void* base, size_t idx)
+{
+    if (BF16) {
+        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + idx);
+        return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+                           __uint_as_float(r.y & 0xFFFF0000u));
+    }
+    return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + idx);
+}
+
+template <int D, bool BF16>
 __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF32 p)
 {
     const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
@@ -672,7 +685,7 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
     const int ctx = min(p.ctx[b], p.max_pages * p.P);
     const int last = ctx - p.S + i;
     const int kvh = h / p.G;
-    const float* qp = p.q + ((size_t)(b * p.S + i) * p.Hq + h) * D;
+    const size_t qoff = ((size_t)(b * p.S + i) * p.Hq + h) * D;
     const int32_t* tab = p.table + (size_t)b * p.max_pages;
     float o[D];
 #pragma unroll
@@ -681,13 +694,11 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
     for (int t = lane; t <= last; t += 64) {
         const int pg = min(max(tab[t / p.P], 0), p.num_pages - 1);   // never read outside the pool
         const size_t off = (size_t)pg * p.page_stride + kvh * p.head_stride + (t % p.P) * p.token_stride;
-        const float* kp = p.k + off;
-        const float* vp = p.v + off;
         float dot = 0.f;
 #pragma unroll
         for (int d = 0; d < D; d += 4) {
-            const float4 kk = *reinterpret_cast<const float4*>(kp + d);
-            const float4 qq = *reinterpret_cast<const float4*>(qp + d);
+            const float4 kk = load4<BF16>(p.k, off + d);
+            const float4 qq = load4<BF16>(p.q, qoff + d);
             dot += kk.x * qq.x + kk.y * qq.y + kk.z * qq.z + kk.w * qq.w;
         }
         const float s = dot * p.scale_log2;
@@ -697,7 +708,7 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
         l = l * alpha + pv;
 #pragma unroll
         for (int d = 0; d < D; d += 4) {
-            const float4 vv = *reinterpret_cast<const float4*>(vp + d);
+            const float4 vv = load4<BF16>(p.v, off + d);
             o[d] = o[d] * alpha + pv * vv.x;
             o[d + 1] = o[d + 1] * alpha + pv * vv.y;
             o[d + 2] = o[d + 2] * alpha + pv * vv.z;
@@ -719,13 +730,22 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
     }
     if (lane == 0) {
         const float inv = 1.f / l;
-        float* op = p.out + ((size_t)(b * p.S + i) * p.Hq + h) * D;
+        if (BF16) {
+            __bf16* op = static_cast<__bf16*>(p.out) + qoff;
 #pragma unroll
-        for (int d = 0; d < D; ++d) op[d] = o[d] * inv;
+            for (int d = 0; d < D; ++d) op[d] = (__bf16)(o[d] * inv);
+        } else {
+            float* op = static_cast<float*>(p.out) + qoff;
+#pragma unroll
+            for (int d = 0; d < D; ++d) op[d] = o[d] * inv;
+        }
     }
 }
 
 // ---- host side ----------------------------------------------------------------------------
+
+// bf16 at D = 128 runs on the MFMA kernels; fp32, and bf16 at D = 64, on the plain one
+static bool uses_mfma_path(int32_t D, int32_t dtype) { return dtype != IDLM_DTYPE_F32 && D == 128; }
 
 static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
                       int32_t max_pages, int32_t dtype, int* err)
@@ -739,11 +759,10 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
         P != 16 || max_pages < 1 || (int64_t)max_pages * P >= (1 << 30) ||
         (int64_t)B * max_pages >= (1LL << 31)) { *err = IDLM_ERR_SHAPE; return false; }
     const int G = Hq / Hkv;
-    if (dtype != IDLM_DTYPE_F32) {
-        if (D != 128) { *err = IDLM_ERR_DTYPE; return false; }
+    if (uses_mfma_path(D, dtype)) {
         if (S * G > 256) { *err = IDLM_ERR_SHAPE; return false; }
     } else {
-        if (D != 64 && D != 128) { *err = IDLM_ERR_DTYPE; return false; }
+        if ((D != 64 && D != 128) || dtype == IDLM_DTYPE_BF16_KOP) { *err = IDLM_ERR_DTYPE; return false; }
         if (Hq > 65535) { *err = IDLM_ERR_SHAPE; return false; }
     }
     return true;
@@ -768,7 +787,7 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
 {
     int err;
     if (!shapes_ok(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, &err)) return 0;
-    if (dtype == IDLM_DTYPE_F32 || B == 0) return 0;
+    if (!uses_mfma_path(D, dtype) || B == 0) return 0;
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
     // two partial slots of 16*NB rows per wavefront of the largest grid
@@ -801,20 +820,19 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int G = Hq / Hkv;
 
-    if (dtype == IDLM_DTYPE_F32) {
+    if (!uses_mfma_path(D, dtype)) {
         AttnParamsF32 p;
-        p.q = static_cast<const float*>(q);
-        p.k = static_cast<const float*>(k_cache);
-        p.v = static_cast<const float*>(v_cache);
-        p.table = block_table; p.ctx = ctx_lens; p.out = static_cast<float*>(out);
+        p.q = q; p.k = k_cache; p.v = v_cache;
+        p.table = block_table; p.ctx = ctx_lens; p.out = out;
         p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.P = P; p.max_pages = max_pages_per_seq; p.num_pages = num_pages;
         p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
         p.scale_log2 = scale * kLog2e;
         (void)hipGetLastError();
         dim3 grid(Hq, S, B);
         if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
-        if (D == 64) hipLaunchKernelGGL(isd_attention_f32_kernel<64>, grid, dim3(64), 0, st, p);
-        else hipLaunchKernelGGL(isd_attention_f32_kernel<128>, grid, dim3(64), 0, st, p);
+        if (dtype == IDLM_DTYPE_BF16) hipLaunchKernelGGL((isd_attention_f32_kernel<64, true>), grid, dim3(64), 0, st, p);
+        else if (D == 64) hipLaunchKernelGGL((isd_attention_f32_kernel<64, false>), grid, dim3(64), 0, st, p);
+        else hipLaunchKernelGGL((isd_attention_f32_kernel<128, false>), grid, dim3(64), 0, st, p);
         if (events) {
             (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
             (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);

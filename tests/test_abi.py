@@ -46,7 +46,7 @@ def test_workspace_sizes_are_host_only_and_monotone():
     assert w > 0
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 2) == w   # operand-order K pages: same kernels
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 0) == 0   # fp32 path needs none
-    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64 unsupported
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64: the plain path needs none
     assert idlm.idlm_isd_attention_workspace(256, 33, 32, 8, 128, 16, 512, 1) == 0
 
 
@@ -70,7 +70,7 @@ def _attention(**kw):
     (dict(S=0), -2), (dict(S=33), -2), (dict(Hq=7), -2), (dict(P=32), -2), (dict(max_pages=0), -2),
     (dict(S=32, Hq=32, Hkv=2), -2),            # S*G = 512 rows
     (dict(nwg=-1), -2), (dict(nwg=5000), -2), (dict(ts=64), -2),
-    (dict(dtype=7), -3), (dict(D=64), -3), (dict(D=96, dtype=0), -3),
+    (dict(dtype=7), -3), (dict(D=96), -3), (dict(D=96, dtype=0), -3),
     (dict(dtype=2, D=64), -3), (dict(dtype=2, ts=256, hs=128, ps=16 * 256), -3),   # operand-order K pages need D = token_stride = 128
     (dict(q=ODD), -4), (dict(k=ODD), -4), (dict(ts=132), -4),
     (dict(), -5),                              # bf16 path without a workspace
