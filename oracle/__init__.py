@@ -59,6 +59,10 @@ def lib() -> C.CDLL:
                                                  C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
                                                  C.c_double, C.c_double, C.c_int32, C.c_double, C.c_int32] + [C.c_void_p] * 7
         L.isd_oracle_accept_filtered.restype = C.c_int
+        L.isd_oracle_accept_filtered_q.argtypes = [C.c_void_p] * 4 + [C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32,
+                                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                                   C.c_double, C.c_double, C.c_int32, C.c_double, C.c_int32] + [C.c_void_p] * 10
+        L.isd_oracle_accept_filtered_q.restype = C.c_int
         L.isd_oracle_kv_append.argtypes = [C.c_void_p] * 6 + [C.c_int32] * 7 + [C.c_int64] * 3 + [C.c_int32]
         L.isd_oracle_kv_append.restype = C.c_int
         L.isd_oracle_commit.argtypes = [C.c_void_p] * 8 + [C.c_int32] + [C.c_void_p] * 5 + [C.c_int32] * 6
@@ -298,6 +302,46 @@ def accept_filtered(logits, draft_tokens, rng_seed, *, n_draft, top_k, top_p=1.0
         raise ValueError("isd_oracle_accept_filtered failed: %d" % rc)
     return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, kept=kept, accept_margin=margin,
                 sample_gap=gap, runner_up=runner, proposal_gap=pgap, cut_margin=cut)
+
+
+def accept_filtered_q(logits, draft_tokens, rng_seed, *, n_draft, top_k, top_p=1.0, q_logits=None, q_row=None, greedy=None,
+                      rng_offset=0, temperature=1.0, tau=0.0, sample_proposals=False):
+    """Acceptance under the filtered sampling distribution with drafts drawn from the filtered distribution
+    of q_logits[b, q_row[b] + j, :] (isd_oracle_accept_filtered_q; q_logits None: point mass).  Returns the
+    outputs of `accept_filtered` plus draft_q [B,S-1], q_cut_margin [B,S-1] and resid_small [B]."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, S, V = logits.shape
+    ncol = S - 1
+    dt = None
+    if S > 1:
+        dt = np.ascontiguousarray(np.ascontiguousarray(draft_tokens, dtype=np.int32)[:, :ncol])
+    nd_arr, nd_uni = None, 0
+    if np.isscalar(n_draft):
+        nd_uni = int(n_draft)
+    else:
+        nd_arr = np.ascontiguousarray(n_draft, dtype=np.int32)
+    ql = qr = None
+    if q_logits is not None:
+        ql = np.ascontiguousarray(q_logits, dtype=np.float32)
+        assert ql.shape == logits.shape
+        qr = np.ascontiguousarray(q_row, dtype=np.int32)
+        assert qr.shape == (B,)
+    g = None if greedy is None else np.ascontiguousarray(greedy, dtype=np.uint8)
+    accept_len = np.zeros(B, dtype=np.int32); new_tokens = np.zeros((B, S), dtype=np.int32)
+    probs = np.zeros((B, max(ncol, 0))); dq = np.zeros((B, max(ncol, 0))); margin = np.zeros((B, max(ncol, 0)))
+    kept = np.zeros((B, S), dtype=np.int32); gap = np.zeros(B); runner = np.zeros(B, dtype=np.int32); pgap = np.zeros((B, S))
+    cut = np.zeros((B, S)); qcut = np.zeros((B, max(ncol, 0))); small = np.zeros(B)
+    rc = lib().isd_oracle_accept_filtered_q(_ptr(logits), _ptr(dt), _ptr(ql), _ptr(qr), int(rng_seed), _ptr(accept_len),
+                                            _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(g), int(rng_offset),
+                                            float(temperature), float(tau), int(top_k), float(top_p),
+                                            1 if sample_proposals else 0, _ptr(probs) if ncol else None,
+                                            _ptr(dq) if ncol else None, _ptr(kept), _ptr(margin) if ncol else None,
+                                            _ptr(gap), _ptr(runner), _ptr(pgap), _ptr(cut), _ptr(qcut) if ncol else None,
+                                            _ptr(small))
+    if rc != 0:
+        raise ValueError("isd_oracle_accept_filtered_q failed: %d" % rc)
+    return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, draft_q=dq, kept=kept, accept_margin=margin,
+                sample_gap=gap, runner_up=runner, proposal_gap=pgap, cut_margin=cut, q_cut_margin=qcut, resid_small=small)
 
 
 def gated_lora_linear(x, W, A, Bm, gate, *, sel=None) -> np.ndarray:

@@ -18,6 +18,9 @@
  *   - acceptance with general proposal distributions (Alg. 1 as printed: drafts
  *     sampled from q, accept with probability min(1, p/q), residual
  *     normalize(max(0, p - q))), sampling temperature and the relaxed threshold.
+ *   - acceptance under the filtered sampling distribution of the paper's runs (App. H:
+ *     temperature, top-k, top-p), with point-mass proposals or with drafts drawn from the
+ *     filtered distribution of the row that proposed them.
  *   - the counter-based generator Philox4x32-10 (Salmon et al., SC'11) that
  *     supplies the uniforms of the accept test and of the Gumbel-max sampler.
  *   - the two steps that close the loop between consecutive ISD steps (Sec. 3.3
@@ -561,32 +564,54 @@ static int filtered_row(const float* l, int V, double T, int top_k, double top_p
     return keep;
 }
 
+/* Probability of vocabulary id x under a filtered row (0 outside the kept set). */
+static double filtered_prob_of(const int32_t* idx, const double* prob, int cnt, int x)
+{
+    for (int c = 0; c < cnt; ++c)
+        if (idx[c] == x) return prob[c];
+    return 0.0;
+}
+
 /*
- * Alg. 1 with point-mass (arg-max or sampled-then-fixed) proposals under the filtered sampling
- * distribution pf_j of every row (see filtered_row): accept draft x_j iff
- * u < min(1, (1+tau) pf_j(x_j)) (greedy sequences: x_j == arg-max), resample on the first
- * rejection from pf_r without x_r, bonus token from pf_D, proposals of the rows after the
- * drafts: arg-max, or (sample_proposals) a draw from pf_j with random stream 2.  Draws are
- * Gumbel-max over the kept elements with the noise of their vocabulary ids, so that the
- * unfiltered case (top_k >= V, top_p = 1) reproduces isd_oracle_accept_general.
+ * Alg. 1 under the filtered sampling distribution pf_j of every row (see filtered_row), with
+ * point-mass proposals (q_logits == NULL: the deployed setting, q_j(x_j) = 1) or with proposals
+ * drawn from the filtered distribution qf_j of the row that proposed them (Alg. 1 as printed,
+ * Sec. 3.2 "Adaptive stride via p/q acceptance", under the sampler of App. H:
+ * qf_j = filter(q_logits[b, q_row[b] + j, :]) with the same temperature, top_k and top_p):
+ *   accept draft x_j iff u < min(1, (1+tau) pf_j(x_j) / qf_j(x_j)); a draft outside qf_j's
+ *   support (it cannot have been drawn from it) is accepted iff pf_j(x_j) > 0;
+ *   greedy sequences: x_j == arg-max;
+ *   on the first rejection, row r resamples from normalize(max(0, pf_r - qf_r)) (point mass:
+ *   pf_r without x_r); the bonus token after D acceptances is a draw from pf_D;
+ *   proposals of the rows after the drafts: arg-max, or (sample_proposals) a draw from pf_j
+ *   with random stream 2.
+ * Draws are Gumbel-max over the kept elements with the noise of their vocabulary ids, so that
+ * the unfiltered case (top_k >= V, top_p = 1) reproduces isd_oracle_accept_general.
  * Outputs as isd_oracle_accept; kept[b,j] = number of elements of row j that survive the filter;
- * cut_margin[b,j] = distance of the closest cumulative probability from top_p (a single-precision
- * implementation may cut such a row one element earlier or later when this is tiny).
- * A rejection when pf_r has no element other than x_r cannot happen for tau = 0 (pf(x) = 1);
- * should rounding or tau produce it, x_r's row arg-max is emitted.
+ * draft_q[b,j] = qf_j(x_j) (1 for point mass); cut_margin[b,j] (and q_cut_margin[b,j] for the
+ * proposing row of draft j) = distance of the closest cumulative probability from top_p (a
+ * single-precision implementation may cut such a row one element earlier or later when this is
+ * tiny); resid_small[b] = the smaller of pf - qf at the winner and the runner-up of a residual
+ * draw (the difference cancels in single precision when it is tiny), INFINITY otherwise.
+ * A rejection with an empty residual cannot happen for tau = 0 (it needs pf_r <= qf_r
+ * everywhere, hence pf_r == qf_r and a ratio of 1); should rounding or tau produce it, row r's
+ * arg-max is emitted.
  */
-int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                               int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
-                               int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
-                               uint32_t rng_offset, double temperature, double tau, int32_t top_k,
-                               double top_p, int32_t sample_proposals, double* draft_probs, int32_t* kept,
-                               double* accept_margin, double* sample_gap, int32_t* runner_up,
-                               double* proposal_gap, double* cut_margin)
+static int accept_filtered_impl(const float* logits, const int32_t* draft_tokens, const float* q_logits,
+                                const int32_t* q_row, uint64_t rng_seed,
+                                int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                                int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                                uint32_t rng_offset, double temperature, double tau, int32_t top_k,
+                                double top_p, int32_t sample_proposals, double* draft_probs, double* draft_q,
+                                int32_t* kept, double* accept_margin, double* sample_gap, int32_t* runner_up,
+                                double* proposal_gap, double* cut_margin, double* q_cut_margin,
+                                double* resid_small)
 {
     if (!logits || !accept_len || !new_tokens) return ORACLE_ERR_ARG;
     if (B < 0 || S < 1 || V < 1 || !(temperature > 0.0) || !(tau >= 0.0)) return ORACLE_ERR_ARG;
     if (top_k < 1 || !(top_p > 0.0) || !(top_p <= 1.0)) return ORACLE_ERR_ARG;
     if (S > 1 && !draft_tokens) return ORACLE_ERR_ARG;
+    if (q_logits && !q_row) return ORACLE_ERR_ARG;
     const int ncol = S - 1;
     const int K = top_k < V ? top_k : V;
     int status = ORACLE_OK;
@@ -595,6 +620,7 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
     for (int b = 0; b < B; ++b) {
         const int D = n_draft ? n_draft[b] : n_draft_uniform;
         int bad = (D < 0 || D > S - 1);
+        if (!bad && q_logits && D > 0 && (q_row[b] < 0 || q_row[b] + D > S)) bad = 1;
         for (int j = 0; !bad && j < D; ++j) {
             const int x = draft_tokens[(int64_t)b * ncol + j];
             if (x < 0 || x >= V) bad = 1;
@@ -609,6 +635,9 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
         int32_t* idx = (int32_t*)malloc(sizeof(int32_t) * (size_t)S * K);
         double* prob = (double*)malloc(sizeof(double) * (size_t)S * K);
         int* cnt = (int*)malloc(sizeof(int) * S);
+        int32_t* qidx = (int32_t*)malloc(sizeof(int32_t) * (size_t)S * K);   /* proposing row of draft j */
+        double* qprob = (double*)malloc(sizeof(double) * (size_t)S * K);
+        int* qcnt = (int*)malloc(sizeof(int) * S);
         for (int j = 0; j < S; ++j) {
             cnt[j] = filtered_row(logits + ((int64_t)b * S + j) * V, V, temperature, top_k, top_p, work,
                                   idx + (size_t)j * K, prob + (size_t)j * K,
@@ -617,21 +646,27 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
         }
         for (int j = 0; j < ncol; ++j) {
             if (draft_probs) draft_probs[(int64_t)b * ncol + j] = 0.0;
+            if (draft_q) draft_q[(int64_t)b * ncol + j] = 0.0;
             if (accept_margin) accept_margin[(int64_t)b * ncol + j] = INFINITY;
+            if (q_cut_margin) q_cut_margin[(int64_t)b * ncol + j] = INFINITY;
         }
+        for (int j = 0; q_logits && j < D; ++j)
+            qcnt[j] = filtered_row(q_logits + ((int64_t)b * S + q_row[b] + j) * V, V, temperature, top_k, top_p, work,
+                                   qidx + (size_t)j * K, qprob + (size_t)j * K,
+                                   q_cut_margin ? q_cut_margin + (int64_t)b * ncol + j : NULL);
         int r = D, open = 1;
         for (int j = 0; j < D; ++j) {
             const int x = draft_tokens[(int64_t)b * ncol + j];
-            double pf = 0.0;
-            for (int c = 0; c < cnt[j]; ++c)
-                if (idx[(size_t)j * K + c] == x) pf = prob[(size_t)j * K + c];
+            const double pf = filtered_prob_of(idx + (size_t)j * K, prob + (size_t)j * K, cnt[j], x);
+            const double qf = q_logits ? filtered_prob_of(qidx + (size_t)j * K, qprob + (size_t)j * K, qcnt[j], x) : 1.0;
             if (draft_probs) draft_probs[(int64_t)b * ncol + j] = pf;
+            if (draft_q) draft_q[(int64_t)b * ncol + j] = qf;
             int ok;
             if (is_greedy) {
                 ok = (x == idx[(size_t)j * K]);
             } else {
                 const double u = isd_oracle_accept_uniform(rng_seed, rng_offset, (uint32_t)(b * S + j));
-                double thr = (1.0 + tau) * pf;
+                double thr = (qf > 0.0) ? (1.0 + tau) * pf / qf : (pf > 0.0 ? INFINITY : 0.0);
                 if (thr > 1.0) thr = 1.0;
                 ok = (u < thr);
                 if (accept_margin) accept_margin[(int64_t)b * ncol + j] = fabs(u - thr);
@@ -641,23 +676,31 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
         accept_len[b] = r;
 
         int fresh = idx[(size_t)r * K];
-        double gap = INFINITY;
+        double gap = INFINITY, small = INFINITY;
         int second = -1;
         if (!is_greedy) {
-            const int excluded = (r < D) ? draft_tokens[(int64_t)b * ncol + r] : -1;
-            double best = -INFINITY, next = -INFINITY;
+            const int x = (r < D) ? draft_tokens[(int64_t)b * ncol + r] : -1;
+            double best = -INFINITY, next = -INFINITY, w_best = INFINITY, w_next = INFINITY;
             int found = -1;
             for (int c = 0; c < cnt[r]; ++c) {
                 const int i = idx[(size_t)r * K + c];
-                if (i == excluded) continue;
-                const double sc = log(prob[(size_t)r * K + c]) + isd_oracle_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + r), (uint32_t)i);
-                if (sc > best || (sc == best && i < found)) { next = best; second = found; best = sc; found = i; }
-                else if (sc > next) { next = sc; second = i; }
+                double w = prob[(size_t)r * K + c];            /* bonus token: pf_D itself */
+                if (r < D) {                                   /* residual max(0, pf_r - qf_r) */
+                    const double qv = q_logits ? filtered_prob_of(qidx + (size_t)r * K, qprob + (size_t)r * K, qcnt[r], i)
+                                               : (i == x ? 1.0 : 0.0);
+                    w -= qv;
+                    if (!(w > 0.0)) continue;
+                }
+                const double sc = log(w) + isd_oracle_gumbel(rng_seed, rng_offset, (uint32_t)(b * S + r), (uint32_t)i);
+                if (sc > best || (sc == best && i < found)) { next = best; second = found; w_next = w_best; best = sc; found = i; w_best = w; }
+                else if (sc > next) { next = sc; second = i; w_next = w; }
             }
             if (found >= 0) { fresh = found; gap = best - next; }
+            if (r < D && q_logits && found >= 0) small = w_best < w_next ? w_best : w_next;
         }
         if (sample_gap) sample_gap[b] = gap;
         if (runner_up) runner_up[b] = second;
+        if (resid_small) resid_small[b] = small;
 
         for (int j = 0; j < S; ++j) {
             int32_t tok;
@@ -680,9 +723,41 @@ int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens,
             new_tokens[(int64_t)b * S + j] = tok;
             if (proposal_gap) proposal_gap[(int64_t)b * S + j] = pg;
         }
-        free(work); free(idx); free(prob); free(cnt);
+        free(work); free(idx); free(prob); free(cnt); free(qidx); free(qprob); free(qcnt);
     }
     return status;
+}
+
+/* Point-mass proposals (the deployed setting). */
+int isd_oracle_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                               int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                               int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                               uint32_t rng_offset, double temperature, double tau, int32_t top_k,
+                               double top_p, int32_t sample_proposals, double* draft_probs, int32_t* kept,
+                               double* accept_margin, double* sample_gap, int32_t* runner_up,
+                               double* proposal_gap, double* cut_margin)
+{
+    return accept_filtered_impl(logits, draft_tokens, NULL, NULL, rng_seed, accept_len, new_tokens, B, S, V,
+                                n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
+                                sample_proposals, draft_probs, NULL, kept, accept_margin, sample_gap, runner_up,
+                                proposal_gap, cut_margin, NULL, NULL);
+}
+
+/* Proposals drawn from the filtered distribution of q_logits[b, q_row[b] + j, :] (NULL: point mass). */
+int isd_oracle_accept_filtered_q(const float* logits, const int32_t* draft_tokens, const float* q_logits,
+                                 const int32_t* q_row, uint64_t rng_seed,
+                                 int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                                 int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                                 uint32_t rng_offset, double temperature, double tau, int32_t top_k,
+                                 double top_p, int32_t sample_proposals, double* draft_probs, double* draft_q,
+                                 int32_t* kept, double* accept_margin, double* sample_gap, int32_t* runner_up,
+                                 double* proposal_gap, double* cut_margin, double* q_cut_margin,
+                                 double* resid_small)
+{
+    return accept_filtered_impl(logits, draft_tokens, q_logits, q_row, rng_seed, accept_len, new_tokens, B, S, V,
+                                n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
+                                sample_proposals, draft_probs, draft_q, kept, accept_margin, sample_gap, runner_up,
+                                proposal_gap, cut_margin, q_cut_margin, resid_small);
 }
 
 /* ------------------------------------------------------------------------ */
