@@ -283,6 +283,42 @@ int idlm_isd_accept_filtered(const float* logits, const int32_t* draft_tokens, u
 size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32_t V);
 
 /*
+ * idlm_isd_accept_filtered_q - idlm_isd_accept_filtered for drafts that were DRAWN from the
+ * filtered distribution of the row that proposed them (sample_proposals of the previous call):
+ * Alg. 1 as printed (Sec. 3.2 "Adaptive stride via p/q acceptance") under the sampler of App. H.
+ * With qf_j the filtered distribution (same temperature, top_k, top_p) of the proposing row of
+ * draft j:
+ *   accept_j = greedy[b] ? (x_j == argmax) : (u_{b,j} < min(1, (1+tau) pf_j(x_j) / qf_j(x_j)));
+ *               a draft outside qf_j's support (it cannot have been drawn from it) is accepted
+ *               iff pf_j(x_j) > 0
+ *   fresh token after a rejection at row r: a draw from normalize(max(0, pf_r - qf_r)), i.e.
+ *               argmax over the ids kept in pf_r with pf_r(i) > qf_r(i) of
+ *               ln(pf_r(i) - qf_r(i)) + Gumbel noise of id i; the arg-max if there is none
+ *   everything else as idlm_isd_accept_filtered, which is the case q_cand == NULL.
+ * For tau = 0 the emitted token is distributed as pf_r whatever qf_r was.
+ *
+ * The proposer is not passed as logits but as the record this call keeps of every row: the
+ * row's top_k (value, id) pairs, 64 x 8 bytes per row, so the previous step's logits are never
+ * read again.
+ * cand_out   uint64 [B,S,64] out or NULL: the record of this call's rows (opaque; entries beyond
+ *            top_k are 0).  Given, it also replaces the workspace (which may then be NULL).
+ * q_cand     uint64 [B,S,64] or NULL: cand_out of the call that proposed the drafts, made with
+ *            the same top_k; must not be the buffer passed as cand_out.  NULL = point mass.
+ * q_row      int32 [B] (required with q_cand): row of q_cand that proposed draft 0 of sequence
+ *            b; draft j came from row q_row[b]+j (forced into the sequence's S rows).
+ * draft_q    fp32 [B,S-1] out or NULL: qf_j(x_j) (1 for point mass, 0 outside the support).
+ * Single precision: pf - qf cancels when the two are close, so a residual draw whose winner
+ * has a tiny residual may differ from double-precision arithmetic.
+ */
+int idlm_isd_accept_filtered_q(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+                               const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len,
+                               int32_t* new_tokens, int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform,
+                               const int32_t* n_draft, const uint8_t* greedy, uint32_t rng_offset,
+                               float temperature, float tau, int32_t top_k, float top_p,
+                               int32_t sample_proposals, float* draft_probs, float* draft_q, int32_t* kept,
+                               uint64_t* cand_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * idlm_isd_kv_append - batched scatter of the stride's K/V rows into the paged cache, before the
  * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): "KV slots
  * are allocated via a single batched scatter").

@@ -68,6 +68,9 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_filtered.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                                C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept_filtered.restype = C.c_int
+        L.idlm_isd_accept_filtered_q.argtypes = [vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
+                                                 C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.idlm_isd_accept_filtered_q.restype = C.c_int
         L.idlm_isd_accept_filtered_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_filtered_workspace.restype = C.c_size_t
         L.idlm_isd_kv_append.argtypes = [vp] * 6 + [i32] * 7 + [i64] * 3 + [i32, vp]
@@ -317,6 +320,39 @@ def idlm_isd_accept_filtered(logits, draft_tokens, rng_seed, accept_len, new_tok
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_accept_filtered")
+
+
+def idlm_isd_accept_filtered_q(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, top_k, top_p=1.0,
+                               q_cand=None, q_row=None, greedy=None, rng_offset=0, temperature=1.0, tau=0.0,
+                               sample_proposals=False, draft_probs=None, draft_q=None, kept=None, cand_out=None,
+                               workspace=None, stream=None):
+    """Filtered acceptance for drafts drawn from the proposing rows' filtered distributions (see idlm.h);
+    q_cand / cand_out are int64 tensors [B,S,64] (the 64-bit records, opaque)."""
+    B, S, V = logits.shape
+    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    if S > 1:
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, S - 1) and draft_tokens.is_contiguous()
+    nd_uni, nd_arr = (int(n_draft), None) if isinstance(n_draft, int) else (0, n_draft)
+    if nd_arr is not None:
+        assert nd_arr.dtype == torch.int32 and nd_arr.shape == (B,)
+    for a in (draft_probs, draft_q):
+        if a is not None:
+            assert a.dtype == torch.float32 and tuple(a.shape) == (B, S - 1) and a.is_contiguous()
+    if kept is not None:
+        assert kept.dtype == torch.int32 and tuple(kept.shape) == (B, S) and kept.is_contiguous()
+    for a in (q_cand, cand_out):
+        if a is not None:
+            assert a.dtype == torch.int64 and tuple(a.shape) == (B, S, 64) and a.is_contiguous()
+    if q_cand is not None:
+        assert q_row is not None and q_row.dtype == torch.int32 and q_row.shape == (B,)
+    rc = lib().idlm_isd_accept_filtered_q(
+        _ptr(logits), _ptr(draft_tokens) if S > 1 else None, _ptr(q_cand), _ptr(q_row), int(rng_seed), _ptr(accept_len),
+        _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(greedy), int(rng_offset), float(temperature), float(tau),
+        int(top_k), float(top_p), 1 if sample_proposals else 0, _ptr(draft_probs), _ptr(draft_q), _ptr(kept),
+        _ptr(cand_out), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+        _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_accept_filtered_q")
 
 
 def idlm_gated_lora_linear_workspace(T, d_in, d_out, r, tile_tokens=0, k_splits=0) -> int:

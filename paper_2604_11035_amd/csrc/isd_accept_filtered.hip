@@ -1,5 +1,8 @@
 // Acceptance under the filtered sampling distribution of the paper's runs (App. H, ISD
-// configuration table: temperature, top_k 50, top_p 0.95) with point-mass proposals:
+// configuration table: temperature, top_k 50, top_p 0.95) with point-mass proposals, or with
+// drafts drawn from the filtered distribution of the row that proposed them (Alg. 1 as printed,
+// Sec. 3.2; that row's candidates are kept from the call that processed it, 512 bytes per row,
+// so the proposer's logits are never read again):
 //   1. one streaming pass per logit row that keeps the exact top_k (<= 64) elements, in
 //      descending order, equal values by ascending index;
 //   2. per sequence (one wavefront, lane = candidate): temperature, top-p cut, renormalisation,
@@ -150,6 +153,9 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
 struct FilteredParams {
     const int32_t* draft_tokens;
     const unsigned long long* cand;     // [rows][64] keys in descending order, 0 = none
+    const unsigned long long* q_cand;   // the same record of the step that proposed the drafts, or null (point mass)
+    const int32_t* q_row;               // [B] row of q_cand that proposed draft 0
+    float* draft_q;
     int32_t* accept_len;
     int32_t* new_tokens;
     const int32_t* n_draft;
@@ -166,9 +172,10 @@ struct FilteredParams {
 
 // The filtered distribution of one row over the wavefront's lanes: lane c holds candidate c.
 // Returns the number of candidates kept; pf = renormalised probability (0 for lanes not kept).
-__device__ __forceinline__ int filtered_row(const FilteredParams& p, int row, int lane, int& idx, float& pf)
+__device__ __forceinline__ int filtered_row(const FilteredParams& p, const unsigned long long* __restrict__ cand, int row,
+                                            int lane, int& idx, float& pf)
 {
-    const unsigned long long key = p.cand[(size_t)row * kTopKMax + lane];
+    const unsigned long long key = cand[(size_t)row * kTopKMax + lane];
     const int n = __builtin_popcountll(__ballot(key != 0ull));
     idx = key ? key_index(key) : -1;
     const float val = key ? key_value(key) : -INFINITY;
@@ -188,15 +195,15 @@ __device__ __forceinline__ int filtered_row(const FilteredParams& p, int row, in
     return keep;
 }
 
-// Gumbel-max draw among the kept candidates of a row (noise of the candidates' vocabulary ids);
-// `excluded` is left out; returns -1 if nothing qualifies.
-__device__ __forceinline__ int draw(const FilteredParams& p, int row, int stream, int idx, float pf, int excluded)
+// Gumbel-max draw among the candidates of a row with weight > 0 (noise of the candidates'
+// vocabulary ids): argmax of ln(weight) + g; returns -1 if nothing qualifies.
+__device__ __forceinline__ int draw(const FilteredParams& p, int row, int stream, int idx, float weight)
 {
     float score = -INFINITY;
-    if (pf > 0.f && idx != excluded) {
+    if (weight > 0.f) {
         const uint4 w = philox4x32_10(make_uint4((uint32_t)idx >> 2, (uint32_t)row, (uint32_t)stream, p.rng_offset), p.key);
         const uint32_t word = (idx & 3) == 0 ? w.x : (idx & 3) == 1 ? w.y : (idx & 3) == 2 ? w.z : w.w;
-        score = logf(pf) + gumbel(word);
+        score = logf(weight) + gumbel(word);
     }
     int best = score > -INFINITY ? idx : INT_MAX;
 #pragma unroll
@@ -215,6 +222,9 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
     const bool is_greedy = p.greedy ? (p.greedy[b] != 0) : false;
     int D = p.n_draft ? p.n_draft[b] : p.n_draft_uniform;
     D = max(0, min(D, S - 1));
+    const bool has_q = p.q_cand != nullptr;
+    // first proposing row, kept inside the sequence's S rows whatever the array holds
+    const int q0 = has_q ? b * S + max(0, min(p.q_row[b], S - D)) : 0;
 
     // accept tests of the drafts, in order; r = first failure
     int r = D;
@@ -222,24 +232,38 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
         const int row = b * S + j;
         int idx;
         float pf;
-        const int keep = filtered_row(p, row, lane, idx, pf);
+        const int keep = filtered_row(p, p.cand, row, lane, idx, pf);
         if (p.kept && lane == 0) p.kept[row] = keep;
         if (j < ncol) {
-            float px = 0.f;
+            float px = 0.f, qx = 0.f;
             bool ok = true;
             if (j < D) {
                 const int x = p.draft_tokens[(size_t)b * ncol + j];
                 const unsigned long long hit = __ballot(idx == x && pf > 0.f);
                 px = hit ? __shfl(pf, (int)__builtin_ctzll(hit)) : 0.f;
+                qx = 1.f;
+                if (has_q) {
+                    int qi;
+                    float qf;
+                    filtered_row(p, p.q_cand, q0 + j, lane, qi, qf);
+                    const unsigned long long qhit = __ballot(qi == x && qf > 0.f);
+                    qx = qhit ? __shfl(qf, (int)__builtin_ctzll(qhit)) : 0.f;
+                }
                 if (is_greedy) {
                     ok = (x == __shfl(idx, 0));
                 } else {
                     const uint4 w = philox4x32_10(make_uint4(0u, (uint32_t)row, 0u, p.rng_offset), p.key);
-                    ok = unit_uniform(w.x) < fminf(1.f, p.one_plus_tau * px);
+                    // a draft outside the proposer's support cannot have been drawn from it: the
+                    // ratio is taken as infinite if the anchor keeps the token, as zero otherwise
+                    const float thr = qx > 0.f ? fminf(1.f, p.one_plus_tau * px / qx) : (px > 0.f ? 1.f : 0.f);
+                    ok = unit_uniform(w.x) < thr;
                 }
                 if (!ok && j < r) r = j;
             }
-            if (p.draft_probs && lane == 0) p.draft_probs[(size_t)b * ncol + j] = px;
+            if (lane == 0) {
+                if (p.draft_probs) p.draft_probs[(size_t)b * ncol + j] = px;
+                if (p.draft_q) p.draft_q[(size_t)b * ncol + j] = qx;
+            }
         }
     }
     if (lane == 0) p.accept_len[b] = r;
@@ -253,16 +277,32 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
         else {
             int idx;
             float pf;
-            filtered_row(p, row, lane, idx, pf);
+            filtered_row(p, p.cand, row, lane, idx, pf);
             const int top = __shfl(idx, 0);
             tok = top;
             if (!is_greedy) {
                 if (j == r) {
-                    const int excluded = (r < D) ? p.draft_tokens[(size_t)b * ncol + r] : -1;
-                    const int got = draw(p, row, 1, idx, pf, excluded);
+                    // bonus token: a draw from pf; after a rejection: from max(0, pf - qf)
+                    // (point mass: pf without the draft)
+                    float weight = pf;
+                    if (r < D && has_q) {
+                        int qi;
+                        float qf;
+                        filtered_row(p, p.q_cand, q0 + r, lane, qi, qf);
+                        float mine = 0.f;
+                        for (int t = 0; t < kTopKMax; ++t) {
+                            const int id = __shfl(qi, t);
+                            const float v = __shfl(qf, t);
+                            if (id == idx && id >= 0) mine = v;
+                        }
+                        weight = pf - mine;
+                    } else if (r < D) {
+                        if (idx == p.draft_tokens[(size_t)b * ncol + r]) weight = 0.f;
+                    }
+                    const int got = draw(p, row, 1, idx, weight);
                     if (got >= 0) tok = got;
                 } else if (p.sample_proposals) {
-                    const int got = draw(p, row, 2, idx, pf, -1);
+                    const int got = draw(p, row, 2, idx, pf);
                     if (got >= 0) tok = got;
                 }
             }
@@ -282,12 +322,12 @@ extern "C" size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32
     return align256((size_t)B * S * kTopKMax * sizeof(unsigned long long));
 }
 
-extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                                        int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
-                                        int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
-                                        uint32_t rng_offset, float temperature, float tau, int32_t top_k, float top_p,
-                                        int32_t sample_proposals, float* draft_probs, int32_t* kept,
-                                        void* workspace, size_t workspace_bytes, void* stream)
+static int accept_filtered_impl(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+                                const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len, int32_t* new_tokens,
+                                int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                const uint8_t* greedy, uint32_t rng_offset, float temperature, float tau, int32_t top_k,
+                                float top_p, int32_t sample_proposals, float* draft_probs, float* draft_q, int32_t* kept,
+                                uint64_t* cand_out, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
     if (!n_draft && (n_draft_uniform < 0 || n_draft_uniform > S - 1)) return IDLM_ERR_SHAPE;
@@ -296,14 +336,23 @@ extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draf
     if (B == 0) return IDLM_OK;
     if (!logits || !accept_len || !new_tokens) return IDLM_ERR_NULL;
     if (S > 1 && !draft_tokens) return IDLM_ERR_NULL;
-    if (!aligned(logits, 16)) return IDLM_ERR_ALIGN;
-    const size_t need = idlm_isd_accept_filtered_workspace(B, S, V);
-    if (!workspace || workspace_bytes < need) return IDLM_ERR_WORKSPACE;
-    if (!aligned(workspace, 256)) return IDLM_ERR_ALIGN;
+    if (q_cand && !q_row) return IDLM_ERR_NULL;
+    if (!aligned(logits, 16) || !aligned(q_cand, 8) || !aligned(cand_out, 8)) return IDLM_ERR_ALIGN;
+    if (q_cand && q_cand == cand_out) return IDLM_ERR_SHAPE;     // the proposer's record is read while this one is written
+    unsigned long long* cand = reinterpret_cast<unsigned long long*>(cand_out);
+    if (!cand) {
+        const size_t need = idlm_isd_accept_filtered_workspace(B, S, V);
+        if (!workspace || workspace_bytes < need) return IDLM_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return IDLM_ERR_ALIGN;
+        cand = static_cast<unsigned long long*>(workspace);
+    }
 
     FilteredParams p;
     p.draft_tokens = draft_tokens;
-    p.cand = static_cast<unsigned long long*>(workspace);
+    p.cand = cand;
+    p.q_cand = reinterpret_cast<const unsigned long long*>(q_cand);
+    p.q_row = q_row;
+    p.draft_q = draft_q;
     p.accept_len = accept_len; p.new_tokens = new_tokens; p.n_draft = n_draft; p.greedy = greedy;
     p.draft_probs = draft_probs; p.kept = kept;
     p.key = make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32));
@@ -315,7 +364,32 @@ extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draf
     hipStream_t st = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     hipLaunchKernelGGL(isd_row_topk_kernel<16>, dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
-                       top_k < V ? top_k : V, static_cast<unsigned long long*>(workspace));
+                       top_k < V ? top_k : V, cand);
     hipLaunchKernelGGL(isd_accept_filtered_chain_kernel, dim3((unsigned)B), dim3(64), 0, st, p);
     return launch_status();
+}
+
+extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                        int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S, int32_t V,
+                                        int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                                        uint32_t rng_offset, float temperature, float tau, int32_t top_k, float top_p,
+                                        int32_t sample_proposals, float* draft_probs, int32_t* kept,
+                                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    return accept_filtered_impl(logits, draft_tokens, nullptr, nullptr, rng_seed, accept_len, new_tokens, B, S, V,
+                                n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
+                                sample_proposals, draft_probs, nullptr, kept, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int idlm_isd_accept_filtered_q(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+                                          const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len,
+                                          int32_t* new_tokens, int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform,
+                                          const int32_t* n_draft, const uint8_t* greedy, uint32_t rng_offset,
+                                          float temperature, float tau, int32_t top_k, float top_p,
+                                          int32_t sample_proposals, float* draft_probs, float* draft_q, int32_t* kept,
+                                          uint64_t* cand_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return accept_filtered_impl(logits, draft_tokens, q_cand, q_row, rng_seed, accept_len, new_tokens, B, S, V,
+                                n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
+                                sample_proposals, draft_probs, draft_q, kept, cand_out, workspace, workspace_bytes, stream);
 }

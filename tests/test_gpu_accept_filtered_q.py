@@ -1,0 +1,157 @@
+"""GPU parity of idlm_isd_accept_filtered_q (filtered acceptance with drafts drawn from the proposing rows'
+filtered distributions) with the CPU oracle through the C ABI, as two consecutive calls: the first proposes
+(sampled proposals, keeps its candidate records), the second verifies those drafts against the records.
+Sequences the oracle marks as too close to call in single precision are skipped and counted."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_11035_amd as idlm
+from helpers import GAP_MARGIN, PROB_ABS_TOL
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CUT_MARGIN = 1e-5
+RATIO_MARGIN = 3e-5        # |u - min(1, (1+tau) pf/qf)| below this: within single-precision evaluation error
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def call(logits, drafts, n_draft, greedy, seed, off, T, tau, top_k, top_p, samp, q_cand=None, q_row=None, keep_record=True,
+         workspace=False):
+    B, S, V = logits.shape
+    accept_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    new_tokens = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+    probs = torch.full((B, max(S - 1, 1)), -7.0, device=DEV)[:, :S - 1].contiguous()
+    dq = torch.full((B, max(S - 1, 1)), -7.0, device=DEV)[:, :S - 1].contiguous()
+    kept = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+    cand = torch.full((B, S, 64), -1, dtype=torch.int64, device=DEV) if keep_record else None
+    ws = torch.empty(max(256, idlm.idlm_isd_accept_filtered_workspace(B, S, V)), dtype=torch.uint8, device=DEV) if workspace else None
+    idlm.idlm_isd_accept_filtered_q(dev(logits), dev(drafts) if S > 1 else None, seed, accept_len, new_tokens, n_draft=dev(n_draft),
+                                    top_k=top_k, top_p=top_p, q_cand=q_cand, q_row=dev(q_row), greedy=dev(greedy), rng_offset=off,
+                                    temperature=T, tau=tau, sample_proposals=samp, draft_probs=probs if S > 1 else None,
+                                    draft_q=dq if S > 1 else None, kept=kept, cand_out=cand, workspace=ws)
+    torch.cuda.synchronize()
+    return dict(accept_len=accept_len.cpu().numpy(), new_tokens=new_tokens.cpu().numpy(), draft_probs=probs.cpu().numpy(),
+                draft_q=dq.cpu().numpy(), kept=kept.cpu().numpy()), cand
+
+
+def compare(g, r, n_draft, greedy, with_q):
+    B, S = g["new_tokens"].shape
+    skipped = 0
+    for b in range(B):
+        D = n_draft[b]
+        if (r["cut_margin"][b] < CUT_MARGIN).any() or (with_q and (r["q_cut_margin"][b, :D] < CUT_MARGIN).any()):
+            skipped += 1
+            continue
+        assert np.array_equal(g["kept"][b], r["kept"][b]), b
+        if S > 1:
+            assert np.abs(g["draft_probs"][b] - r["draft_probs"][b]).max() <= PROB_ABS_TOL
+            assert np.abs(g["draft_q"][b] - r["draft_q"][b]).max() <= PROB_ABS_TOL
+        decisive = r["accept_margin"][b, :min(D, r["accept_len"][b] + 1)]
+        if (decisive < RATIO_MARGIN).any():
+            skipped += 1
+            continue
+        assert g["accept_len"][b] == r["accept_len"][b], b
+        rr = r["accept_len"][b]
+        for j in range(S):
+            got, want = g["new_tokens"][b, j], r["new_tokens"][b, j]
+            if j == rr and not greedy[b]:
+                if got != want:
+                    # ln(pf - qf) carries an absolute error of about 4e-7 / (pf - qf) in single precision
+                    slack = GAP_MARGIN + 2e-6 / max(r["resid_small"][b], 1e-12) if np.isfinite(r["resid_small"][b]) else GAP_MARGIN
+                    assert r["sample_gap"][b] < slack and got == r["runner_up"][b], (b, j, got, want, r["sample_gap"][b], slack)
+                    skipped += 1
+            elif j > D and np.isfinite(r["proposal_gap"][b, j]):
+                if got != want:
+                    assert r["proposal_gap"][b, j] < GAP_MARGIN, (b, j)
+                    skipped += 1
+            else:
+                assert got == want, (b, j, got, want)
+    return skipped
+
+
+def two_steps(rng, B, S, V, T, tau, top_k, top_p, sigma=1.0, stray=0.05):
+    """Step A: rows 1.. of q_logits propose by sampling (nothing to verify); step B verifies those drafts."""
+    q_logits = (rng.standard_normal((B, S, V)) * 3).astype(np.float32)
+    zero = np.zeros(B, np.int32)
+    none = np.zeros(B, np.uint8)
+    ra = oracle.accept_filtered_q(q_logits, np.zeros((B, S - 1), np.int32), 21, n_draft=zero, top_k=top_k, top_p=top_p, greedy=none,
+                                  rng_offset=1, temperature=T, tau=tau, sample_proposals=True)
+    ga, record = call(q_logits, np.zeros((B, S - 1), np.int32), zero, none, 21, 1, T, tau, top_k, top_p, True)
+    assert compare(ga, ra, zero, none, False) <= 2
+    # the anchor rows of step B: row j verifies the draft that row 1 + j proposed, so it resembles that row
+    logits = (rng.standard_normal((B, S, V)) * 3).astype(np.float32)
+    logits[:, :S - 1] = q_logits[:, 1:] + sigma * rng.standard_normal((B, S - 1, V)).astype(np.float32)
+    drafts = ra["new_tokens"][:, 1:].astype(np.int32).copy()            # the oracle's draws (the GPU's may differ at a near tie)
+    far = rng.random((B, S - 1)) < stray                                 # a few tokens the proposer never drew
+    drafts = np.where(far, rng.integers(0, V, size=(B, S - 1)), drafts).astype(np.int32)
+    n_draft = rng.integers(0, S, size=B).astype(np.int32)
+    greedy = (rng.random(B) < 0.2).astype(np.uint8)
+    q_row = np.ones(B, np.int32)
+    rb = oracle.accept_filtered_q(logits, drafts, 22, n_draft=n_draft, top_k=top_k, top_p=top_p, q_logits=q_logits, q_row=q_row,
+                                  greedy=greedy, rng_offset=2, temperature=T, tau=tau, sample_proposals=True)
+    gb, _ = call(logits, drafts, n_draft, greedy, 22, 2, T, tau, top_k, top_p, True, q_cand=record, q_row=q_row)
+    return gb, rb, n_draft, greedy, (logits, drafts, q_logits, record)
+
+
+@pytest.mark.parametrize("T,tau,top_k,top_p", [(1.0, 0.0, 50, 0.95), (0.7, 0.2, 8, 0.9), (1.3, 0.0, 64, 1.0), (1.0, 0.0, 3, 0.5)])
+def test_verifying_sampled_drafts_matches_the_oracle(T, tau, top_k, top_p):
+    rng = np.random.default_rng(top_k * 3 + int(T * 10))
+    B, S, V = 96, 8, 8192
+    g, r, n_draft, greedy, _ = two_steps(rng, B, S, V, T, tau, top_k, top_p)
+    assert compare(g, r, n_draft, greedy, True) <= 5
+    live = greedy == 0
+    assert ((r["accept_len"] < n_draft) & live).sum() >= 3 and ((r["accept_len"] == n_draft) & live & (n_draft > 0)).sum() >= 3
+    used = np.arange(S - 1)[None] < n_draft[:, None]
+    assert ((r["draft_q"] == 0) & used).sum() >= 3
+    if top_k >= 8:
+        assert ((r["draft_q"] > 0) & (r["draft_q"] < 1) & used).sum() > 50
+
+
+def test_identical_rows_accept_every_sampled_draft_and_workspace_form():
+    """Anchor rows equal to the proposing rows: the ratio is 1 and nothing is rejected; also the form that keeps no
+    record (candidates in the workspace), and q_cand = None, which is idlm_isd_accept_filtered."""
+    rng = np.random.default_rng(5)
+    B, S, V = 32, 6, 4096
+    g, r, n_draft, greedy, (logits, drafts, q_logits, record) = two_steps(rng, B, S, V, 1.0, 0.0, 50, 0.95, sigma=0.0, stray=0.0)
+    assert compare(g, r, n_draft, greedy, True) <= 1
+    live = greedy == 0
+    assert (r["accept_len"][live] == n_draft[live]).all() and (g["accept_len"][live] == n_draft[live]).all()
+    q_row = np.ones(B, np.int32)
+    g2, none = call(logits, drafts, n_draft, greedy, 22, 2, 1.0, 0.0, 50, 0.95, True, q_cand=record, q_row=q_row, keep_record=False,
+                    workspace=True)
+    assert none is None
+    for k in g:
+        assert np.array_equal(g[k], g2[k]), k
+    # point mass through the same entry point: the outputs of idlm_isd_accept_filtered
+    g3, _ = call(logits, drafts, n_draft, greedy, 22, 2, 1.0, 0.0, 50, 0.95, True)
+    al = torch.zeros(B, dtype=torch.int32, device=DEV); nt = torch.zeros((B, S), dtype=torch.int32, device=DEV)
+    ws = torch.empty(idlm.idlm_isd_accept_filtered_workspace(B, S, V), dtype=torch.uint8, device=DEV)
+    idlm.idlm_isd_accept_filtered(dev(logits), dev(drafts), 22, al, nt, n_draft=dev(n_draft), top_k=50, top_p=0.95, greedy=dev(greedy),
+                                  rng_offset=2, sample_proposals=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(g3["accept_len"], al.cpu().numpy()) and np.array_equal(g3["new_tokens"], nt.cpu().numpy())
+    used = np.arange(S - 1)[None] < n_draft[:, None]
+    assert (g3["draft_q"][used] == 1).all()
+
+
+def test_full_vocabulary_and_edge_shapes():
+    rng = np.random.default_rng(17)
+    g, r, n_draft, greedy, _ = two_steps(rng, 6, 4, 151936, 1.0, 0.0, 50, 0.95)
+    assert compare(g, r, n_draft, greedy, True) <= 1
+    g, r, n_draft, greedy, _ = two_steps(rng, 5, 3, 8, 1.0, 0.0, 50, 1.0)            # fewer ids than top_k
+    assert compare(g, r, n_draft, greedy, True) <= 1
+    # q_row outside the stride is forced inside it rather than read out of bounds
+    B, S, V = 4, 4, 1024
+    logits = (rng.standard_normal((B, S, V)) * 2).astype(np.float32)
+    drafts = logits[:, :S - 1].argmax(-1).astype(np.int32)
+    nd = np.full(B, S - 1, np.int32); g0 = np.zeros(B, np.uint8)
+    _, record = call(logits, drafts, np.zeros(B, np.int32), g0, 1, 0, 1.0, 0.0, 20, 0.9, True)
+    ga, _ = call(logits, drafts, nd, g0, 2, 0, 1.0, 0.0, 20, 0.9, False, q_cand=record, q_row=np.full(B, 99, np.int32))
+    gb, _ = call(logits, drafts, nd, g0, 2, 0, 1.0, 0.0, 20, 0.9, False, q_cand=record, q_row=np.full(B, 1, np.int32))
+    for k in ga:
+        assert np.array_equal(ga[k], gb[k]), k
