@@ -78,10 +78,12 @@ def attention_flops(ctx_lens, cfg):
     return 4 * cfg.D * cfg.Hq * vis
 
 
-def cpu_baseline(att, acc, cfg, n_seq):
+def cpu_baseline(att, acc, cfg, n_seq, threads=0):
     """Times the oracle (as it stands) on the first n_seq sequences of the workload."""
     import torch
     import oracle
+    if threads > 0:
+        oracle.set_num_threads(threads)
     from isd_inputs import to_numpy
 
     ctx = att.ctx_lens[:n_seq].cpu().numpy()
@@ -112,8 +114,8 @@ def cpu_baseline(att, acc, cfg, n_seq):
         "unit": "tokens/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": "first %d of %d sequences of serve256 (%d context tokens): attention %.2f s, acceptance %.2f s"
-                  % (n_seq, cfg.B, int(ctx.sum()), t1 - t0, t2 - t1),
+        "sample": "first %d of %d sequences of %s (%d context tokens): attention %.2f s, acceptance %.2f s"
+                  % (n_seq, cfg.B, cfg.name, int(ctx.sum()), t1 - t0, t2 - t1),
     }
 
 
@@ -126,6 +128,7 @@ def main():
     ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
     ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle (0 = all the box gives it)")
     ap.add_argument("--k-operand-order", type=int, default=1,
                     help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
     args = ap.parse_args()
@@ -408,8 +411,8 @@ def main():
                 "paper_serving_shape_64x7": lora_case(64, 7, torch.full((64,), 3, dtype=torch.int32, device=dev))}
 
     cpu = None
-    if args.cpu_sample > 0 and cfg.dtype == "bf16":
-        cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B))
+    if args.cpu_sample > 0:
+        cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B), args.cpu_threads)
 
     line = {
         "metric": "ISD tokens verified+proposed/sec at B=256 on 1 GPU; % of peak HBM GB/s",

@@ -51,6 +51,8 @@ def lib() -> C.CDLL:
         L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.isd_oracle_row_stats.restype = C.c_int
         L.isd_oracle_num_threads.restype = C.c_int
+        L.isd_oracle_set_num_threads.argtypes = [C.c_int]
+        L.isd_oracle_set_num_threads.restype = None
         L.isd_oracle_accept_general.argtypes = [C.c_void_p] * 4 + [C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                                 C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_double,
                                                 C.c_double, C.c_int32] + [C.c_void_p] * 7
@@ -81,6 +83,11 @@ def _ptr(a):
 
 def num_threads() -> int:
     return int(lib().isd_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads used by the oracle's parallel loops from now on (results do not depend on it)."""
+    lib().isd_oracle_set_num_threads(int(n))
 
 
 def philox4x32_10(ctr, key) -> np.ndarray:

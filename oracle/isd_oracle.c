@@ -957,6 +957,17 @@ int isd_oracle_row_stats(const float* row, int32_t V, double* m_out, double* z_o
     return ORACLE_OK;
 }
 
+/* Number of threads the parallel loops use from now on (timing the oracle on one core); no
+ * effect on results: every item is computed by one thread. */
+void isd_oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int isd_oracle_num_threads(void)
 {
     int n = 1;
