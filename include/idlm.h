@@ -213,6 +213,20 @@ int idlm_isd_accept_bf16_ev(const uint16_t* logits, const int32_t* draft_tokens,
                             void* workspace, size_t workspace_bytes, void* stream, void* const* events);
 
 /*
+ * idlm_isd_rng_dump - the random numbers of the acceptance pass, written out (a check, not part
+ * of the step): for r < n_rows and i < V, the uniform u = (2 (x >> 9) + 1) 2^-24 and the Gumbel
+ * noise g = -ln(-ln u) that vocabulary element i of logit row row0 + r draws, x being word i & 3
+ * of Philox4x32-10 at counter (i >> 2, row0 + r, stream_tag, rng_offset) with key (rng_seed low,
+ * high) - the generator Sec. 3.3 (3) leaves open ("Gumbel-max"); stream tags: 0 accept-test
+ * uniform (element 0 of the row), 1 Gumbel noise of the fresh token, 2 of sampled proposals.
+ * uniforms, gumbels  fp32 [n_rows, V] device, out; either may be NULL (not both).
+ * The uniforms are exact (24-bit numerators); the noise is evaluated in single precision.
+ * n_rows <= 65535.  Asynchronous on `stream`; errors as the other calls.
+ */
+int idlm_isd_rng_dump(uint64_t rng_seed, uint32_t rng_offset, int32_t stream_tag, int32_t row0, int32_t n_rows,
+                      int32_t V, float* uniforms, float* gumbels, void* stream);
+
+/*
  * idlm_isd_accept_general - acceptance with general proposal distributions, sampling
  * temperature, relaxed threshold and sampled proposals: Alg. 1 as printed (drafts drawn from
  * q_j, accepted with probability min(1, p_j(x_j)/q_j(x_j)), resampled from

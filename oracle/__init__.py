@@ -51,6 +51,8 @@ def lib() -> C.CDLL:
         L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.isd_oracle_row_stats.restype = C.c_int
         L.isd_oracle_num_threads.restype = C.c_int
+        L.isd_oracle_rng_dump.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.isd_oracle_rng_dump.restype = None
         L.isd_oracle_set_num_threads.argtypes = [C.c_int]
         L.isd_oracle_set_num_threads.restype = None
         L.isd_oracle_accept_general.argtypes = [C.c_void_p] * 4 + [C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -96,6 +98,13 @@ def philox4x32_10(ctr, key) -> np.ndarray:
     out = np.zeros(4, dtype=np.uint32)
     lib().isd_oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
     return out
+
+
+def rng_dump(seed: int, offset: int, stream: int, row0: int, n_rows: int, V: int):
+    """(uniforms, gumbels), float64 [n_rows, V]: what element i of row row0 + r draws under a stream tag."""
+    u = np.zeros((n_rows, V)); g = np.zeros((n_rows, V))
+    lib().isd_oracle_rng_dump(int(seed), int(offset), int(stream), int(row0), n_rows, V, _ptr(u), _ptr(g))
+    return u, g
 
 
 def accept_uniform(seed: int, offset: int, row: int) -> float:

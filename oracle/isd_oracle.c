@@ -96,6 +96,19 @@ static uint32_t rng_word(uint64_t seed, uint32_t offset, uint32_t stream, uint32
     return out[i & 3u];
 }
 
+/* The uniforms (and, if asked, the Gumbel noise -ln(-ln u)) of elements 0..V-1 of rows
+ * row0..row0+n_rows-1 under a stream tag, one by one through rng_word. */
+void isd_oracle_rng_dump(uint64_t seed, uint32_t offset, uint32_t stream, uint32_t row0, int32_t n_rows, int32_t V,
+                         double* uniforms, double* gumbels)
+{
+    for (int r = 0; r < n_rows; ++r)
+        for (int i = 0; i < V; ++i) {
+            const double u = uniform_from_bits(rng_word(seed, offset, stream, row0 + (uint32_t)r, (uint32_t)i));
+            if (uniforms) uniforms[(int64_t)r * V + i] = u;
+            if (gumbels) gumbels[(int64_t)r * V + i] = -log(-log(u));
+        }
+}
+
 double isd_oracle_accept_uniform(uint64_t seed, uint32_t offset, uint32_t row)
 {
     return uniform_from_bits(rng_word(seed, offset, 0u, row, 0u));

@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_filtered_q.argtypes = [vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                                  C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept_filtered_q.restype = C.c_int
+        L.idlm_isd_rng_dump.argtypes = [C.c_uint64, C.c_uint32, i32, i32, i32, i32, vp, vp, vp]
+        L.idlm_isd_rng_dump.restype = C.c_int
         L.idlm_isd_accept_filtered_workspace.argtypes = [i32, i32, i32]
         L.idlm_isd_accept_filtered_workspace.restype = C.c_size_t
         L.idlm_isd_kv_append.argtypes = [vp] * 6 + [i32] * 7 + [i64] * 3 + [i32, vp]
@@ -353,6 +355,17 @@ def idlm_isd_accept_filtered_q(logits, draft_tokens, rng_seed, accept_len, new_t
         _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_accept_filtered_q")
+
+
+def idlm_isd_rng_dump(rng_seed, rng_offset, stream_tag, row0, n_rows, V, *, uniforms=None, gumbels=None, stream=None):
+    """The uniforms / Gumbel noise the acceptance pass draws for rows row0 .. row0+n_rows-1 (see idlm.h)."""
+    for a in (uniforms, gumbels):
+        if a is not None:
+            assert a.dtype == torch.float32 and tuple(a.shape) == (n_rows, V) and a.is_contiguous()
+    rc = lib().idlm_isd_rng_dump(int(rng_seed), int(rng_offset), int(stream_tag), int(row0), int(n_rows), int(V),
+                                 _ptr(uniforms), _ptr(gumbels), _stream(stream))
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_rng_dump")
 
 
 def idlm_gated_lora_linear_workspace(T, d_in, d_out, r, tile_tokens=0, k_splits=0) -> int:

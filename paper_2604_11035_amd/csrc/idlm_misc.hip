@@ -1,6 +1,7 @@
 // Error strings, version, and two plain streaming kernels used to calibrate byte counters and
 // to measure the bandwidth a pure copy / pure read reaches on the device.
 #include "idlm_common.h"
+#include "isd_accept_common.h"
 
 namespace idlm {
 
@@ -30,9 +31,39 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
     if ((threadIdx.x & 63) == 0 && acc == 0x9E3779B9u) atomicXor(sink, acc);
 }
 
+// The uniform and the Gumbel noise that element i of logit row row0 + r draws under a stream tag:
+// the same device functions the acceptance kernels call, written out for inspection.
+__global__ __launch_bounds__(256) void rng_dump_kernel(uint2 key, uint32_t offset, uint32_t stream_tag, uint32_t row0,
+                                                        int V, float* __restrict__ uniforms, float* __restrict__ gumbels)
+{
+    const int r = blockIdx.y;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < V; i += gridDim.x * 256) {
+        const uint4 w = philox4x32_10(make_uint4((uint32_t)i >> 2, row0 + (uint32_t)r, stream_tag, offset), key);
+        const uint32_t word = (i & 3) == 0 ? w.x : (i & 3) == 1 ? w.y : (i & 3) == 2 ? w.z : w.w;
+        if (uniforms) uniforms[(size_t)r * V + i] = unit_uniform(word);
+        if (gumbels) gumbels[(size_t)r * V + i] = gumbel(word);
+    }
+}
+
 }  // namespace idlm
 
 using namespace idlm;
+
+extern "C" int idlm_isd_rng_dump(uint64_t rng_seed, uint32_t rng_offset, int32_t stream_tag, int32_t row0, int32_t n_rows,
+                                 int32_t V, float* uniforms, float* gumbels, void* stream)
+{
+    if (n_rows < 0 || n_rows > 65535 || V < 1 || row0 < 0 || stream_tag < 0 || (int64_t)row0 + n_rows > INT32_MAX)
+        return IDLM_ERR_SHAPE;
+    if (n_rows == 0) return IDLM_OK;
+    if (!uniforms && !gumbels) return IDLM_ERR_NULL;
+    (void)hipGetLastError();
+    const int64_t blocks = ((int64_t)V + 255) / 256;
+    const unsigned gx = (unsigned)(blocks < 1024 ? blocks : 1024);
+    hipLaunchKernelGGL(rng_dump_kernel, dim3(gx, (unsigned)n_rows), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       make_uint2((uint32_t)rng_seed, (uint32_t)(rng_seed >> 32)), rng_offset, (uint32_t)stream_tag,
+                       (uint32_t)row0, V, uniforms, gumbels);
+    return launch_status();
+}
 
 extern "C" const char* idlm_strerror(int code)
 {

@@ -91,3 +91,14 @@ def test_streams_and_rows_are_independent():
     c = np.array([oracle.gumbel(1, 1, 0, i) for i in range(4000)])
     assert abs(np.corrcoef(a, b)[0, 1]) < 0.06
     assert abs(np.corrcoef(a, c)[0, 1]) < 0.06
+
+
+def test_batched_dump_is_the_scalar_functions_element_by_element():
+    u, g = oracle.rng_dump(99, 3, 1, 17, 2, 37)
+    for r in range(2):
+        for i in (0, 1, 2, 3, 4, 35, 36):
+            assert g[r, i] == oracle.gumbel(99, 3, 17 + r, i)
+            word = oracle.philox4x32_10([i >> 2, 17 + r, 1, 3], [99, 0])[i & 3]
+            assert u[r, i] == (2 * (int(word) >> 9) + 1) * 2.0 ** -24
+    u0, _ = oracle.rng_dump(99, 3, 0, 17, 2, 4)
+    assert u0[1, 0] == oracle.accept_uniform(99, 3, 18)
