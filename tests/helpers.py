@@ -72,6 +72,15 @@ def attention_errors(got: np.ndarray, ref: np.ndarray):
     return float((num / den).max()), int(mask.sum())
 
 
+def attention_elementwise_excess(got: np.ndarray, ref: np.ndarray) -> float:
+    """The element-wise view of the same comparison: the smallest c with
+    |got - ref| <= 1e-2 |ref| + c rms(ref) for every element (rms over the element's output vector)."""
+    mask = ~np.isnan(ref).any(axis=-1)
+    g, r = got[mask], ref[mask]
+    rms = np.sqrt((r * r).mean(axis=-1, keepdims=True))
+    return float(((np.abs(g - r) - 1e-2 * np.abs(r)) / rms).max())
+
+
 def as_bf16(logits: torch.Tensor) -> torch.Tensor:
     """The logits as stored by a model that emits bf16 (round to nearest even): input preparation
     for the bf16 entry point; the oracle gets these values widened back to fp32, which is exact."""

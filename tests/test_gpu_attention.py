@@ -23,7 +23,11 @@ def _check(inp, num_workgroups=0, sel=None, scale=0.0, tol=None):
     tol = tol or (h.ATTN_REL_TOL if inp.q.dtype == torch.bfloat16 else h.ATTN_REL_TOL_F32)
     assert nvec > 0
     assert rel <= tol, "max relative error %g over %d vectors" % (rel, nvec)
-    print("max relative error %.3g over %d vectors" % (rel, nvec))
+    excess = h.attention_elementwise_excess(got, ref)
+    print("max relative error %.3g over %d vectors; element-wise excess %.3g rms" % (rel, nvec, excess))
+    # element by element: |err| <= 1e-2 |ref| + c rms(ref); c is set by the rounding of the softmax weights to the MFMA
+    # operand type (2^-9 of a few dominant terms, relative to the vector's scale rather than the element's)
+    assert excess <= (1.5e-2 if inp.q.dtype == torch.bfloat16 else 1e-4), excess
     if inp.q.dtype == torch.bfloat16 and inp.k_cache.is_contiguous() and inp.q.shape[-1] == 128:
         # the same K pool with its pages in operand order: other addresses, the same arithmetic, the same bits
         alt = h.gpu_attention(inp, num_workgroups=num_workgroups, scale=scale, k_operand_order=True)
