@@ -48,23 +48,34 @@ __device__ void sort_buffer_desc(unsigned long long* buf, int n)
         }
 }
 
-// One workgroup per row.  Elements above the current threshold (the K-th largest key seen so
-// far, 0 before K elements have been seen) are appended to a buffer; when the buffer cannot take
-// the next batch it is sorted and cut back to its K largest, which raises the threshold.  On
-// unordered data only a few hundred elements of a 150k row ever pass, so the pass streams.
+// One workgroup per row, exact top K as sorted keys.
+//
+// Fast path (rows in no particular order).  The first batch gives a threshold without sorting
+// anything: every thread takes the maximum of its 64 elements, and the K-th largest of the 256
+// thread maxima is a lower bound of the row's K-th largest element (the K maxima above it are K
+// elements of the row).  About K/256 of the threads, hence a fraction ~ K/(256*64) of the elements,
+// reach it: a few hundred of a 150k row.  The row is then streamed without any barrier; whoever
+// holds such an element appends its key to the buffer through one LDS atomic.  One sort at the end.
+//
+// If the buffer overflows (ascending rows, long runs of equal values), the row is done again by
+// the robust path: elements above the current threshold (the K-th largest key seen so far, 0
+// before K elements have been seen) are appended batch by batch; when the buffer cannot take the
+// next batch it is sorted and cut back to its K largest, which raises the threshold.
 template <int UNROLL>
 __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restrict__ logits, int V, int K,
                                                            unsigned long long* __restrict__ out_keys)
 {
     __shared__ unsigned long long buf[kBufCap];
-    __shared__ int s_count, s_want;
+    __shared__ float s_max[256];
+    __shared__ int s_count, s_want, s_overflow;
     __shared__ unsigned long long s_thr;
+    __shared__ float s_first;
     const int row = blockIdx.x, tid = threadIdx.x;
     const f32x4* __restrict__ p4 = reinterpret_cast<const f32x4*>(logits + (size_t)row * V);
     const int fend = V >> 2;
+    const f32x4 none = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     for (int t = tid; t < kBufCap; t += 256) buf[t] = 0ull;
-    if (tid == 0) { s_count = 0; s_thr = 0ull; }
-    __syncthreads();
+    if (tid == 0) { s_count = 0; s_thr = 0ull; s_overflow = 0; s_first = -INFINITY; }
 
     auto prune = [&]() {           // every thread; buffer -> its K largest, threshold raised
         const int used = s_count;
@@ -79,13 +90,83 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
         }
         __syncthreads();
     };
+    auto write_out = [&]() {
+        if (tid < kTopKMax) out_keys[(size_t)row * kTopKMax + tid] = tid < s_count ? buf[tid] : 0ull;
+    };
 
+    // ---- fast path ----
+    {
+        f32x4 v[UNROLL];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int f = u * 256 + tid;
+            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
+            tmax = fmaxf(tmax, fmaxf(fmaxf(v[u][0], v[u][1]), fmaxf(v[u][2], v[u][3])));
+        }
+        s_max[tid] = tmax;
+        __syncthreads();
+        // position of this thread's maximum among the 256 (equal values: lower thread first), by counting
+        int rank = 0;
+        for (int j = 0; j < 256; ++j) {
+            const float o = s_max[j];
+            rank += (o > tmax || (o == tmax && j < tid)) ? 1 : 0;
+        }
+        if (rank == K - 1) s_first = tmax;
+        __syncthreads();
+        const float thr_v = s_first;
+        const volatile int* overflow = &s_overflow;
+        for (int base = 0; base < fend; base += UNROLL * 256) {
+            if (base) {
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    const int f = base + u * 256 + tid;
+                    v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
+                }
+            }
+            int mine = 0;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const bool in_row = base + u * 256 + tid < fend;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mine += (in_row && v[u][e] >= thr_v) ? 1 : 0;
+            }
+            if (mine) {
+                int slot = atomicAdd(&s_count, mine);
+                if (slot + mine <= kBufCap) {
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        const int f = base + u * 256 + tid;
+                        if (f < fend)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (v[u][e] >= thr_v) buf[slot++] = cand_key(v[u][e], f * 4 + e);
+                    }
+                } else {
+                    s_overflow = 1;
+                }
+            }
+            if (*overflow) break;          // someone ran out of room: the rest of this pass is void
+        }
+        __syncthreads();
+        if (!s_overflow) {
+            prune();
+            write_out();
+            return;
+        }
+        __syncthreads();
+        for (int t = tid; t < kBufCap; t += 256) buf[t] = 0ull;
+        if (tid == 0) { s_count = 0; s_thr = 0ull; }
+        __syncthreads();
+    }
+
+    // ---- robust path ----
     for (int base = 0; base < fend; base += UNROLL * 256) {
         f32x4 v[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int f = base + u * 256 + tid;
-            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
         }
         const unsigned long long thr = s_thr;
         const float thr_v = thr ? key_value(thr) : -INFINITY;
@@ -147,7 +228,7 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
         }
     }
     prune();
-    if (tid < kTopKMax) out_keys[(size_t)row * kTopKMax + tid] = tid < s_count ? buf[tid] : 0ull;
+    write_out();
 }
 
 struct FilteredParams {
