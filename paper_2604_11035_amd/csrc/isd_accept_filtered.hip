@@ -5,7 +5,7 @@
 // so the proposer's logits are never read again):
 //   1. one streaming pass per logit row that keeps the exact top_k (<= 64) elements, in
 //      descending order, equal values by ascending index;
-//   2. per sequence (one wavefront, lane = candidate): temperature, top-p cut, renormalisation,
+//   2. per sequence (one wavefront per row, lane = candidate): temperature, top-p cut, renormalisation,
 //      accept tests, and every draw (fresh token, sampled proposals) as a Gumbel-max over the
 //      at most 64 surviving candidates - no second pass over the logits.
 // HBM-bound: one read of the logits.
@@ -296,9 +296,12 @@ __device__ __forceinline__ int draw(const FilteredParams& p, int row, int stream
     return best == INT_MAX ? -1 : best;
 }
 
-__global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const FilteredParams p)
+constexpr int kChainWaves = 8;     // wavefronts per sequence; rows are dealt out to them in turn
+
+__global__ __launch_bounds__(64 * kChainWaves) void isd_accept_filtered_chain_kernel(const FilteredParams p)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ int s_ok[64];        // accept decision of every draft (S <= 64)
+    const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int S = p.S, ncol = S - 1;
     const bool is_greedy = p.greedy ? (p.greedy[b] != 0) : false;
     int D = p.n_draft ? p.n_draft[b] : p.n_draft_uniform;
@@ -307,10 +310,16 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
     // first proposing row, kept inside the sequence's S rows whatever the array holds
     const int q0 = has_q ? b * S + max(0, min(p.q_row[b], S - D)) : 0;
 
-    // accept tests of the drafts, in order; r = first failure
-    int r = D;
-    for (int j = 0; j < S; ++j) {
+    // accept tests of the drafts, every row on its own
+    for (int j = wave; j < S; j += kChainWaves) {
         const int row = b * S + j;
+        if (j >= D && !p.kept) {        // nothing of this row is needed here
+            if (j < ncol && lane == 0) {
+                if (p.draft_probs) p.draft_probs[(size_t)b * ncol + j] = 0.f;
+                if (p.draft_q) p.draft_q[(size_t)b * ncol + j] = 0.f;
+            }
+            continue;
+        }
         int idx;
         float pf;
         const int keep = filtered_row(p, p.cand, row, lane, idx, pf);
@@ -339,7 +348,7 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
                     const float thr = qx > 0.f ? fminf(1.f, p.one_plus_tau * px / qx) : (px > 0.f ? 1.f : 0.f);
                     ok = unit_uniform(w.x) < thr;
                 }
-                if (!ok && j < r) r = j;
+                if (lane == 0) s_ok[j] = ok ? 1 : 0;
             }
             if (lane == 0) {
                 if (p.draft_probs) p.draft_probs[(size_t)b * ncol + j] = px;
@@ -347,45 +356,48 @@ __global__ __launch_bounds__(64) void isd_accept_filtered_chain_kernel(const Fil
             }
         }
     }
-    if (lane == 0) p.accept_len[b] = r;
+    __syncthreads();
+    int r = D;                      // first failure
+    for (int j = D - 1; j >= 0; --j)
+        if (!s_ok[j]) r = j;
+    if (threadIdx.x == 0) p.accept_len[b] = r;
 
     // tokens
-    for (int j = 0; j < S; ++j) {
+    for (int j = wave; j < S; j += kChainWaves) {
         const int row = b * S + j;
         int tok;
         if (j < r) tok = p.draft_tokens[(size_t)b * ncol + j];
         else if (j > r && j <= D) tok = -1;
-        else {
+        else if (is_greedy || (j != r && !p.sample_proposals)) {
+            tok = key_index(p.cand[(size_t)row * kTopKMax]);        // the arg-max: first key of the row
+        } else {
             int idx;
             float pf;
             filtered_row(p, p.cand, row, lane, idx, pf);
-            const int top = __shfl(idx, 0);
-            tok = top;
-            if (!is_greedy) {
-                if (j == r) {
-                    // bonus token: a draw from pf; after a rejection: from max(0, pf - qf)
-                    // (point mass: pf without the draft)
-                    float weight = pf;
-                    if (r < D && has_q) {
-                        int qi;
-                        float qf;
-                        filtered_row(p, p.q_cand, q0 + r, lane, qi, qf);
-                        float mine = 0.f;
-                        for (int t = 0; t < kTopKMax; ++t) {
-                            const int id = __shfl(qi, t);
-                            const float v = __shfl(qf, t);
-                            if (id == idx && id >= 0) mine = v;
-                        }
-                        weight = pf - mine;
-                    } else if (r < D) {
-                        if (idx == p.draft_tokens[(size_t)b * ncol + r]) weight = 0.f;
+            tok = __shfl(idx, 0);
+            if (j == r) {
+                // bonus token: a draw from pf; after a rejection: from max(0, pf - qf)
+                // (point mass: pf without the draft)
+                float weight = pf;
+                if (r < D && has_q) {
+                    int qi;
+                    float qf;
+                    filtered_row(p, p.q_cand, q0 + r, lane, qi, qf);
+                    float mine = 0.f;
+                    for (int t = 0; t < kTopKMax; ++t) {
+                        const int id = __shfl(qi, t);
+                        const float v = __shfl(qf, t);
+                        if (id == idx && id >= 0) mine = v;
                     }
-                    const int got = draw(p, row, 1, idx, weight);
-                    if (got >= 0) tok = got;
-                } else if (p.sample_proposals) {
-                    const int got = draw(p, row, 2, idx, pf);
-                    if (got >= 0) tok = got;
+                    weight = pf - mine;
+                } else if (r < D) {
+                    if (idx == p.draft_tokens[(size_t)b * ncol + r]) weight = 0.f;
                 }
+                const int got = draw(p, row, 1, idx, weight);
+                if (got >= 0) tok = got;
+            } else {
+                const int got = draw(p, row, 2, idx, pf);
+                if (got >= 0) tok = got;
             }
         }
         if (lane == 0) p.new_tokens[row] = tok;
@@ -446,7 +458,7 @@ static int accept_filtered_impl(const float* logits, const int32_t* draft_tokens
     (void)hipGetLastError();
     hipLaunchKernelGGL(isd_row_topk_kernel<16>, dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
                        top_k < V ? top_k : V, cand);
-    hipLaunchKernelGGL(isd_accept_filtered_chain_kernel, dim3((unsigned)B), dim3(64), 0, st, p);
+    hipLaunchKernelGGL(isd_accept_filtered_chain_kernel, dim3((unsigned)B), dim3(64 * kChainWaves), 0, st, p);
     return launch_status();
 }
 
