@@ -334,8 +334,8 @@ int idlm_isd_accept_filtered_q(const float* logits, const int32_t* draft_tokens,
 
 /*
  * idlm_isd_kv_append - batched scatter of the stride's K/V rows into the paged cache, before the
- * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): "KV slots
- * are allocated via a single batched scatter").
+ * step's attention (Sec. 3.3 (1): every ISD step appends its stride in extend mode; (2): the stride's
+ * KV slots are filled by one scatter for the whole batch).
  *
  * Row i of sequence b belongs to absolute position t = ctx_lens[b]-S+i (ctx_lens counts the S
  * rows, as in idlm_isd_attention) and is copied, for every KV head, to page block_table[b][t/P],

@@ -377,7 +377,7 @@ static void row_lse(const float* l, int V, double T, double* lse, int32_t* arg)
  * the first rejection (Sec. 3.2 "Adaptive stride via p/q acceptance"), with the two
  * knobs the paper's runs use on top: sampling temperature T (App. H: all runs at
  * T = 1, here any T > 0: p = softmax(l/T), q = softmax(l'/T)) and the relaxed
- * threshold of Sec. 5 ("relaxing the acceptance threshold"): accept iff
+ * threshold that Sec. 5 names as a way to trade exactness for speed: accept iff
  * u < min(1, (1+tau) * p/q).
  *
  * q_logits == NULL is the deployed setting (point-mass proposals, q_j(x_j) = 1).
@@ -779,8 +779,8 @@ int isd_oracle_accept_filtered_q(const float* logits, const int32_t* draft_token
 
 /*
  * Batched scatter of the stride's K/V rows into the paged cache (Sec. 3.3 (1):
- * each ISD step appends its 2N-1 tokens in extend mode; (2): "KV slots are
- * allocated via a single batched scatter").  Row i of sequence b belongs to
+ * each ISD step appends its 2N-1 tokens in extend mode; (2): the stride's KV slots
+ * are filled by one scatter for the whole batch).  Row i of sequence b belongs to
  * absolute position t = ctx_lens[b]-S+i (ctx_lens counts the S rows) and goes to
  * page block_table[b][t/P], slot t%P, for every KV head.
  * k_new / v_new [B,S,Hkv,D] contiguous; cache addressing as in attention.
@@ -815,10 +815,10 @@ int isd_oracle_kv_append(const void* k_new, const void* v_new, void* k_cache, vo
 
 /*
  * Trim-and-commit after verification, and the next stride (Alg. 1, last line:
- * "append x_{L+1 : L+n_accepted} to prefix; commit KV cache"; Sec. 3.2: after a
- * rejection "all subsequent tokens are discarded; the next step becomes a pure
- * stride with no tokens to introspect"; Sec. 3.3 (2): the trim-and-commit cycle
- * "frees rejected and MASK positions after each verification").
+ * the accepted tokens join the prefix and their KV entries are committed; Sec. 3.2:
+ * after a rejection everything behind it is dropped and the next step only proposes,
+ * with nothing to introspect; Sec. 3.3 (2): the trim-and-commit cycle gives back the
+ * slots of rejected and MASK positions after every verification).
  *
  * For sequence b with D = n_draft[b] drafts verified this step and r =
  * accept_len[b] of them accepted (0 <= r <= D <= S-1):
