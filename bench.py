@@ -362,6 +362,23 @@ def main():
         gen["filtered_with_sampled_proposals_ms"] = timed(lambda: idlm.idlm_isd_accept_filtered(
             acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft, greedy=acc.greedy, top_k=50,
             top_p=0.95, sample_proposals=True, workspace=ws_f), n=5)
+        # the paper's sampler with sampled drafts, two calls in a row: the first keeps its candidate record,
+        # the second verifies against it (and, last, the same over bf16 logits)
+        rec = [torch.zeros((B, S, 64), dtype=torch.int64, device=dev) for _ in range(2)]
+        q_row1 = torch.ones(B, dtype=torch.int32, device=dev)
+        idlm.idlm_isd_accept_filtered_q(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=0, greedy=acc.greedy,
+                                        top_k=50, top_p=0.95, sample_proposals=True, cand_out=rec[0])
+        nd_q = acc.n_draft.clamp(max=S - 1)
+        gen["filtered_sampled_drafts_verified_ms"] = timed(lambda: idlm.idlm_isd_accept_filtered_q(
+            acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=nd_q, greedy=acc.greedy, top_k=50, top_p=0.95,
+            sample_proposals=True, q_cand=rec[0], q_row=q_row1, cand_out=rec[1]), n=5)
+        if V % 8 == 0:
+            lg16f = acc.logits.to(torch.bfloat16)
+            gen["filtered_sampled_drafts_verified_bf16_logits_ms"] = timed(lambda: idlm.idlm_isd_accept_filtered_q(
+                lg16f, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=nd_q, greedy=acc.greedy, top_k=50, top_p=0.95,
+                sample_proposals=True, q_cand=rec[0], q_row=q_row1, cand_out=rec[1]), n=5)
+            del lg16f
+        del rec
 
     # the acceptance pass over the same logits stored as bf16 (half the bytes per row); not the timed path,
     # whose logits are fp32 as the metric's workload states

@@ -314,6 +314,9 @@ size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32_t V);
  * The proposer is not passed as logits but as the record this call keeps of every row: the
  * row's top_k (value, id) pairs, 64 x 8 bytes per row, so the previous step's logits are never
  * read again.
+ * logits, logits_dtype  IDLM_DTYPE_F32: fp32 [B,S,V], V % 4 == 0; IDLM_DTYPE_BF16: raw bf16 [B,S,V],
+ *            V % 8 == 0 - half the bytes to stream; every value widens exactly to fp32 and the
+ *            results are those of the fp32 call on the widened values (as idlm_isd_accept_bf16).
  * cand_out   uint64 [B,S,64] out or NULL: the record of this call's rows (opaque; entries beyond
  *            top_k are 0).  Given, it also replaces the workspace (which may then be NULL).
  * q_cand     uint64 [B,S,64] or NULL: cand_out of the call that proposed the drafts, made with
@@ -324,7 +327,7 @@ size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32_t V);
  * Single precision: pf - qf cancels when the two are close, so a residual draw whose winner
  * has a tiny residual may differ from double-precision arithmetic.
  */
-int idlm_isd_accept_filtered_q(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+int idlm_isd_accept_filtered_q(const void* logits, int32_t logits_dtype, const int32_t* draft_tokens, const uint64_t* q_cand,
                                const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len,
                                int32_t* new_tokens, int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform,
                                const int32_t* n_draft, const uint8_t* greedy, uint32_t rng_offset,

@@ -68,7 +68,7 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept_filtered.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                                C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept_filtered.restype = C.c_int
-        L.idlm_isd_accept_filtered_q.argtypes = [vp, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
+        L.idlm_isd_accept_filtered_q.argtypes = [vp, i32, vp, vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                                  C.c_float, C.c_float, i32, C.c_float, i32, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.idlm_isd_accept_filtered_q.restype = C.c_int
         L.idlm_isd_rng_dump.argtypes = [C.c_uint64, C.c_uint32, i32, i32, i32, i32, vp, vp, vp]
@@ -329,9 +329,9 @@ def idlm_isd_accept_filtered_q(logits, draft_tokens, rng_seed, accept_len, new_t
                                sample_proposals=False, draft_probs=None, draft_q=None, kept=None, cand_out=None,
                                workspace=None, stream=None):
     """Filtered acceptance for drafts drawn from the proposing rows' filtered distributions (see idlm.h);
-    q_cand / cand_out are int64 tensors [B,S,64] (the 64-bit records, opaque)."""
+    logits fp32 or bf16 [B,S,V]; q_cand / cand_out are int64 tensors [B,S,64] (the 64-bit records, opaque)."""
     B, S, V = logits.shape
-    assert logits.dtype == torch.float32 and logits.is_contiguous()
+    assert logits.dtype in (torch.float32, torch.bfloat16) and logits.is_contiguous()
     if S > 1:
         assert draft_tokens.dtype == torch.int32 and draft_tokens.shape == (B, S - 1) and draft_tokens.is_contiguous()
     nd_uni, nd_arr = (int(n_draft), None) if isinstance(n_draft, int) else (0, n_draft)
@@ -348,7 +348,7 @@ def idlm_isd_accept_filtered_q(logits, draft_tokens, rng_seed, accept_len, new_t
     if q_cand is not None:
         assert q_row is not None and q_row.dtype == torch.int32 and q_row.shape == (B,)
     rc = lib().idlm_isd_accept_filtered_q(
-        _ptr(logits), _ptr(draft_tokens) if S > 1 else None, _ptr(q_cand), _ptr(q_row), int(rng_seed), _ptr(accept_len),
+        _ptr(logits), 1 if logits.dtype == torch.bfloat16 else 0, _ptr(draft_tokens) if S > 1 else None, _ptr(q_cand), _ptr(q_row), int(rng_seed), _ptr(accept_len),
         _ptr(new_tokens), B, S, V, nd_uni, _ptr(nd_arr), _ptr(greedy), int(rng_offset), float(temperature), float(tau),
         int(top_k), float(top_p), 1 if sample_proposals else 0, _ptr(draft_probs), _ptr(draft_q), _ptr(kept),
         _ptr(cand_out), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),

@@ -61,19 +61,26 @@ __device__ void sort_buffer_desc(unsigned long long* buf, int n)
 // the robust path: elements above the current threshold (the K-th largest key seen so far, 0
 // before K elements have been seen) are appended batch by batch; when the buffer cannot take the
 // next batch it is sorted and cut back to its K largest, which raises the threshold.
-template <int UNROLL>
-__global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restrict__ logits, int V, int K,
+template <bool BF16> __device__ __forceinline__ typename LogitVec<BF16>::raw vec_of_minus_inf();
+template <> __device__ __forceinline__ f32x4 vec_of_minus_inf<false>() { return f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY}; }
+template <> __device__ __forceinline__ u32x4 vec_of_minus_inf<true>() { return u32x4{0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u}; }
+
+template <int UNROLL, bool BF16>
+__global__ __launch_bounds__(256) void isd_row_topk_kernel(const void* __restrict__ logits, int V, int K,
                                                            unsigned long long* __restrict__ out_keys)
 {
+    typedef LogitVec<BF16> LV;
+    typedef typename LV::raw raw_t;
+    constexpr int N = LV::N;
     __shared__ unsigned long long buf[kBufCap];
     __shared__ float s_max[256];
     __shared__ int s_count, s_want, s_overflow;
     __shared__ unsigned long long s_thr;
     __shared__ float s_first;
     const int row = blockIdx.x, tid = threadIdx.x;
-    const f32x4* __restrict__ p4 = reinterpret_cast<const f32x4*>(logits + (size_t)row * V);
-    const int fend = V >> 2;
-    const f32x4 none = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    const raw_t* __restrict__ pv = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits) + (size_t)row * V * (16 / N));
+    const int fend = V / N;
+    const raw_t none = vec_of_minus_inf<BF16>();
     for (int t = tid; t < kBufCap; t += 256) buf[t] = 0ull;
     if (tid == 0) { s_count = 0; s_thr = 0ull; s_overflow = 0; s_first = -INFINITY; }
 
@@ -96,13 +103,16 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
 
     // ---- fast path ----
     {
-        f32x4 v[UNROLL];
+        raw_t v[UNROLL];
         float tmax = -INFINITY;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int f = u * 256 + tid;
-            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
-            tmax = fmaxf(tmax, fmaxf(fmaxf(v[u][0], v[u][1]), fmaxf(v[u][2], v[u][3])));
+            v[u] = f < fend ? __builtin_nontemporal_load(pv + f) : none;
+            float e[N];
+            LV::unpack(v[u], e);
+#pragma unroll
+            for (int i = 0; i < N; ++i) tmax = fmaxf(tmax, e[i]);
         }
         s_max[tid] = tmax;
         __syncthreads();
@@ -121,15 +131,17 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     const int f = base + u * 256 + tid;
-                    v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
+                    v[u] = f < fend ? __builtin_nontemporal_load(pv + f) : none;
                 }
             }
             int mine = 0;
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const bool in_row = base + u * 256 + tid < fend;
+                float e[N];
+                LV::unpack(v[u], e);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) mine += (in_row && v[u][e] >= thr_v) ? 1 : 0;
+                for (int i = 0; i < N; ++i) mine += (in_row && e[i] >= thr_v) ? 1 : 0;
             }
             if (mine) {
                 int slot = atomicAdd(&s_count, mine);
@@ -137,10 +149,16 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
 #pragma unroll
                     for (int u = 0; u < UNROLL; ++u) {
                         const int f = base + u * 256 + tid;
-                        if (f < fend)
+                        if (f < fend) {
+                            // unpacked again from the loaded vector: keeping the counting loop's values alive
+                            // until here would double the registers of the bf16 form
+                            asm volatile("" : "+v"(v[u]));
+                            float e[N];
+                            LV::unpack(v[u], e);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (v[u][e] >= thr_v) buf[slot++] = cand_key(v[u][e], f * 4 + e);
+                            for (int i = 0; i < N; ++i)
+                                if (e[i] >= thr_v) buf[slot++] = cand_key(e[i], f * N + i);
+                        }
                     }
                 } else {
                     s_overflow = 1;
@@ -160,13 +178,14 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
         __syncthreads();
     }
 
-    // ---- robust path ----
-    for (int base = 0; base < fend; base += UNROLL * 256) {
-        f32x4 v[UNROLL];
+    // ---- robust path (rare; four loads at a time keeps its registers below the fast path's) ----
+    constexpr int RU = 4;
+    for (int base = 0; base < fend; base += RU * 256) {
+        raw_t v[RU];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < RU; ++u) {
             const int f = base + u * 256 + tid;
-            v[u] = f < fend ? __builtin_nontemporal_load(p4 + f) : none;
+            v[u] = f < fend ? __builtin_nontemporal_load(pv + f) : none;
         }
         const unsigned long long thr = s_thr;
         const float thr_v = thr ? key_value(thr) : -INFINITY;
@@ -175,9 +194,12 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
         // test is only paid by the few that get this far
         int mine = 0;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
+        for (int u = 0; u < RU; ++u) {
+            float e[N];
+            LV::unpack(v[u], e);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) mine += (v[u][e] >= thr_v) ? 1 : 0;
+            for (int i = 0; i < N; ++i) mine += (e[i] >= thr_v) ? 1 : 0;
+        }
         if (tid == 0) s_want = 0;
         if (!__syncthreads_or(mine)) continue;       // nothing in this batch reaches the threshold
         if (mine) atomicAdd(&s_want, mine);
@@ -187,23 +209,29 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
             if (mine) {
                 int exact = 0;
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
+                for (int u = 0; u < RU; ++u) {
                     const int f = base + u * 256 + tid;
-                    if (f < fend)
+                    if (f < fend) {
+                        float e[N];
+                        LV::unpack(v[u], e);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            exact += (v[u][e] >= thr_v && cand_key(v[u][e], f * 4 + e) > thr) ? 1 : 0;
+                        for (int i = 0; i < N; ++i)
+                            exact += (e[i] >= thr_v && cand_key(e[i], f * N + i) > thr) ? 1 : 0;
+                    }
                 }
                 int slot = exact ? atomicAdd(&s_count, exact) : 0;
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
+                for (int u = 0; u < RU; ++u) {
                     const int f = base + u * 256 + tid;
-                    if (f < fend)
+                    if (f < fend) {
+                        float e[N];
+                        LV::unpack(v[u], e);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const unsigned long long key = cand_key(v[u][e], f * 4 + e);
-                            if (v[u][e] >= thr_v && key > thr) buf[slot++] = key;
+                        for (int i = 0; i < N; ++i) {
+                            const unsigned long long key = cand_key(e[i], f * N + i);
+                            if (e[i] >= thr_v && key > thr) buf[slot++] = key;
                         }
+                    }
                 }
             }
             __syncthreads();
@@ -211,19 +239,24 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const float* __restri
             // too many for the buffer (the first batch of a row, or adversarially ordered data): 1024
             // elements at a time, cutting the buffer back as soon as it holds 1024 keys
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                if (s_count >= 1024) prune();
-                else __syncthreads();
-                const unsigned long long t2 = s_thr;
+            for (int u = 0; u < RU; ++u) {
+                float e[N];
+                LV::unpack(v[u], e);
                 const int f = base + u * 256 + tid;
-                if (f < fend) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const unsigned long long key = cand_key(v[u][e], f * 4 + e);
-                        if (key > t2) buf[atomicAdd(&s_count, 1)] = key;
+                for (int h = 0; h < N / 4; ++h) {     // 1024 elements per round
+                    if (s_count >= 1024) prune();
+                    else __syncthreads();
+                    const unsigned long long t2 = s_thr;
+                    if (f < fend) {
+#pragma unroll
+                        for (int i = 4 * h; i < 4 * h + 4; ++i) {
+                            const unsigned long long key = cand_key(e[i], f * N + i);
+                            if (key > t2) buf[atomicAdd(&s_count, 1)] = key;
+                        }
                     }
+                    __syncthreads();
                 }
-                __syncthreads();
             }
         }
     }
@@ -415,14 +448,16 @@ extern "C" size_t idlm_isd_accept_filtered_workspace(int32_t B, int32_t S, int32
     return align256((size_t)B * S * kTopKMax * sizeof(unsigned long long));
 }
 
-static int accept_filtered_impl(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+static int accept_filtered_impl(const void* logits, int32_t logits_dtype, const int32_t* draft_tokens, const uint64_t* q_cand,
                                 const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len, int32_t* new_tokens,
                                 int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
                                 const uint8_t* greedy, uint32_t rng_offset, float temperature, float tau, int32_t top_k,
                                 float top_p, int32_t sample_proposals, float* draft_probs, float* draft_q, int32_t* kept,
                                 uint64_t* cand_out, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
+    if (logits_dtype != IDLM_DTYPE_F32 && logits_dtype != IDLM_DTYPE_BF16) return IDLM_ERR_DTYPE;
+    const int per_vec = logits_dtype == IDLM_DTYPE_BF16 ? 8 : 4;     // elements per 16-byte load
+    if (B < 0 || S < 1 || S > 64 || V < per_vec || (V % per_vec) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
     if (!n_draft && (n_draft_uniform < 0 || n_draft_uniform > S - 1)) return IDLM_ERR_SHAPE;
     if (!(temperature > 0.f) || !(tau >= 0.f) || !(temperature < INFINITY) || !(tau < INFINITY)) return IDLM_ERR_SHAPE;
     if (top_k < 1 || top_k > kTopKMax || !(top_p > 0.f) || !(top_p <= 1.f)) return IDLM_ERR_SHAPE;
@@ -456,8 +491,12 @@ static int accept_filtered_impl(const float* logits, const int32_t* draft_tokens
     p.top_p = top_p;
     hipStream_t st = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(isd_row_topk_kernel<16>, dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
-                       top_k < V ? top_k : V, cand);
+    if (logits_dtype == IDLM_DTYPE_BF16)
+        hipLaunchKernelGGL((isd_row_topk_kernel<16, true>), dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
+                           top_k < V ? top_k : V, cand);
+    else
+        hipLaunchKernelGGL((isd_row_topk_kernel<16, false>), dim3((unsigned)(B * S)), dim3(256), 0, st, logits, V,
+                           top_k < V ? top_k : V, cand);
     hipLaunchKernelGGL(isd_accept_filtered_chain_kernel, dim3((unsigned)B), dim3(64 * kChainWaves), 0, st, p);
     return launch_status();
 }
@@ -469,12 +508,12 @@ extern "C" int idlm_isd_accept_filtered(const float* logits, const int32_t* draf
                                         int32_t sample_proposals, float* draft_probs, int32_t* kept,
                                         void* workspace, size_t workspace_bytes, void* stream)
 {
-    return accept_filtered_impl(logits, draft_tokens, nullptr, nullptr, rng_seed, accept_len, new_tokens, B, S, V,
+    return accept_filtered_impl(logits, IDLM_DTYPE_F32, draft_tokens, nullptr, nullptr, rng_seed, accept_len, new_tokens, B, S, V,
                                 n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
                                 sample_proposals, draft_probs, nullptr, kept, nullptr, workspace, workspace_bytes, stream);
 }
 
-extern "C" int idlm_isd_accept_filtered_q(const float* logits, const int32_t* draft_tokens, const uint64_t* q_cand,
+extern "C" int idlm_isd_accept_filtered_q(const void* logits, int32_t logits_dtype, const int32_t* draft_tokens, const uint64_t* q_cand,
                                           const int32_t* q_row, uint64_t rng_seed, int32_t* accept_len,
                                           int32_t* new_tokens, int32_t B, int32_t S, int32_t V, int32_t n_draft_uniform,
                                           const int32_t* n_draft, const uint8_t* greedy, uint32_t rng_offset,
@@ -482,7 +521,7 @@ extern "C" int idlm_isd_accept_filtered_q(const float* logits, const int32_t* dr
                                           int32_t sample_proposals, float* draft_probs, float* draft_q, int32_t* kept,
                                           uint64_t* cand_out, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return accept_filtered_impl(logits, draft_tokens, q_cand, q_row, rng_seed, accept_len, new_tokens, B, S, V,
+    return accept_filtered_impl(logits, logits_dtype, draft_tokens, q_cand, q_row, rng_seed, accept_len, new_tokens, B, S, V,
                                 n_draft_uniform, n_draft, greedy, rng_offset, temperature, tau, top_k, top_p,
                                 sample_proposals, draft_probs, draft_q, kept, cand_out, workspace, workspace_bytes, stream);
 }

@@ -232,11 +232,11 @@ def test_filtered_accept_workspace_and_empty_batch():
 
 
 def _filtered_q(**kw):
-    a = dict(logits=FAKE, drafts=FAKE, q_cand=None, q_row=None, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024, ndu=1, nd=None,
+    a = dict(logits=FAKE, dtype=0, drafts=FAKE, q_cand=None, q_row=None, seed=1, alen=FAKE, toks=FAKE, B=2, S=4, V=1024, ndu=1, nd=None,
              greedy=None, off=0, T=1.0, tau=0.0, top_k=50, top_p=0.95, samp=0, probs=None, dq=None, kept=None, cand_out=None,
              ws=None, ws_bytes=0, stream=None)
     a.update(kw)
-    return idlm.lib().idlm_isd_accept_filtered_q(a["logits"], a["drafts"], a["q_cand"], a["q_row"], a["seed"], a["alen"],
+    return idlm.lib().idlm_isd_accept_filtered_q(a["logits"], a["dtype"], a["drafts"], a["q_cand"], a["q_row"], a["seed"], a["alen"],
                                                  a["toks"], a["B"], a["S"], a["V"], a["ndu"], a["nd"], a["greedy"], a["off"],
                                                  a["T"], a["tau"], a["top_k"], a["top_p"], a["samp"], a["probs"], a["dq"],
                                                  a["kept"], a["cand_out"], a["ws"], a["ws_bytes"], a["stream"])
@@ -245,6 +245,7 @@ def _filtered_q(**kw):
 @pytest.mark.parametrize("kw,code", [
     (dict(logits=None), -1), (dict(q_cand=FAKE), -1),                       # proposer records without their row index
     (dict(top_k=65), -2), (dict(T=0.0), -2),
+    (dict(dtype=2), -3), (dict(dtype=1, V=1028), -2), (dict(dtype=1, V=1032), -5),    # bf16 rows: whole 16-byte loads of 8 values
     (dict(q_cand=FAKE, q_row=FAKE, cand_out=FAKE), -2),                     # the proposer's record would be overwritten
     (dict(q_cand=ODD, q_row=FAKE), -4), (dict(cand_out=ODD), -4),
     (dict(), -5), (dict(q_cand=FAKE, q_row=FAKE), -5),                      # neither cand_out nor a workspace

@@ -21,7 +21,7 @@ def dev(a):
 
 
 def call(logits, drafts, n_draft, greedy, seed, off, T, tau, top_k, top_p, samp, q_cand=None, q_row=None, keep_record=True,
-         workspace=False):
+         workspace=False, bf16=False):
     B, S, V = logits.shape
     accept_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
     new_tokens = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
@@ -30,7 +30,8 @@ def call(logits, drafts, n_draft, greedy, seed, off, T, tau, top_k, top_p, samp,
     kept = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
     cand = torch.full((B, S, 64), -1, dtype=torch.int64, device=DEV) if keep_record else None
     ws = torch.empty(max(256, idlm.idlm_isd_accept_filtered_workspace(B, S, V)), dtype=torch.uint8, device=DEV) if workspace else None
-    idlm.idlm_isd_accept_filtered_q(dev(logits), dev(drafts) if S > 1 else None, seed, accept_len, new_tokens, n_draft=dev(n_draft),
+    lg = dev(logits).to(torch.bfloat16) if bf16 else dev(logits)
+    idlm.idlm_isd_accept_filtered_q(lg, dev(drafts) if S > 1 else None, seed, accept_len, new_tokens, n_draft=dev(n_draft),
                                     top_k=top_k, top_p=top_p, q_cand=q_cand, q_row=dev(q_row), greedy=dev(greedy), rng_offset=off,
                                     temperature=T, tau=tau, sample_proposals=samp, draft_probs=probs if S > 1 else None,
                                     draft_q=dq if S > 1 else None, kept=kept, cand_out=cand, workspace=ws)
@@ -155,3 +156,55 @@ def test_full_vocabulary_and_edge_shapes():
     gb, _ = call(logits, drafts, nd, g0, 2, 0, 1.0, 0.0, 20, 0.9, False, q_cand=record, q_row=np.full(B, 1, np.int32))
     for k in ga:
         assert np.array_equal(ga[k], gb[k]), k
+
+
+def as_bf16_values(a):
+    """The fp32 values that survive rounding to bf16 (what a model that emits bf16 logits hands over)."""
+    return torch.from_numpy(a).to(torch.bfloat16).float().numpy()
+
+
+@pytest.mark.parametrize("V", [8192, 151936, 1032])
+def test_bf16_logits_give_the_results_of_the_widened_values(V):
+    """bf16 rows hold many equal values, also at the top-k cut (lowest index first): the call on bf16 logits must
+    equal, bit for bit, the fp32 call on the same values, and that one the oracle."""
+    rng = np.random.default_rng(V)
+    B, S = (48, 8) if V < 100000 else (6, 4)
+    q_logits = as_bf16_values((rng.standard_normal((B, S, V)) * 3).astype(np.float32))
+    logits = (rng.standard_normal((B, S, V)) * 3).astype(np.float32)
+    logits[:, :S - 1] = q_logits[:, 1:] + rng.standard_normal((B, S - 1, V)).astype(np.float32)
+    logits = as_bf16_values(logits)
+    zero = np.zeros(B, np.int32); none = np.zeros(B, np.uint8)
+    ra = oracle.accept_filtered_q(q_logits, np.zeros((B, S - 1), np.int32), 3, n_draft=zero, top_k=50, top_p=0.95, greedy=none,
+                                  sample_proposals=True)
+    ga32, rec32 = call(q_logits, np.zeros((B, S - 1), np.int32), zero, none, 3, 0, 1.0, 0.0, 50, 0.95, True)
+    ga16, rec16 = call(q_logits, np.zeros((B, S - 1), np.int32), zero, none, 3, 0, 1.0, 0.0, 50, 0.95, True, bf16=True)
+    assert torch.equal(rec32, rec16)
+    for k in ga32:
+        assert np.array_equal(ga32[k], ga16[k]), k
+    assert compare(ga16, ra, zero, none, False) <= 2
+    drafts = ra["new_tokens"][:, 1:].astype(np.int32).copy()
+    n_draft = rng.integers(0, S, size=B).astype(np.int32)
+    greedy = (rng.random(B) < 0.2).astype(np.uint8)
+    q_row = np.ones(B, np.int32)
+    rb = oracle.accept_filtered_q(logits, drafts, 4, n_draft=n_draft, top_k=50, top_p=0.95, q_logits=q_logits, q_row=q_row,
+                                  greedy=greedy, sample_proposals=True)
+    gb32, _ = call(logits, drafts, n_draft, greedy, 4, 0, 1.0, 0.0, 50, 0.95, True, q_cand=rec32, q_row=q_row)
+    gb16, _ = call(logits, drafts, n_draft, greedy, 4, 0, 1.0, 0.0, 50, 0.95, True, q_cand=rec16, q_row=q_row, bf16=True)
+    for k in gb32:
+        assert np.array_equal(gb32[k], gb16[k]), k
+    assert compare(gb16, rb, n_draft, greedy, True) <= 3
+    # the rounding made ties: some row holds equal values among its kept ids
+    top = np.sort(q_logits.reshape(B * S, V), axis=-1)[:, -50:]
+    assert (np.diff(top, axis=-1) == 0).any()
+
+
+def test_bf16_rows_in_adverse_order():
+    B, S, V, K = 3, 2, 20000, 50
+    base = np.arange(V, dtype=np.float32) / 1000.0
+    for row in (base, base[::-1].copy(), np.zeros(V, np.float32)):
+        logits = as_bf16_values(np.broadcast_to(row, (B, S, V)).copy())
+        nd = np.zeros(B, np.int32); g0 = np.zeros(B, np.uint8)
+        r = oracle.accept_filtered_q(logits, np.zeros((B, S - 1), np.int32), 2, n_draft=nd, top_k=K, top_p=1.0, greedy=g0,
+                                     sample_proposals=True)
+        g, _ = call(logits, np.zeros((B, S - 1), np.int32), nd, g0, 2, 0, 1.0, 0.0, K, 1.0, True, bf16=True)
+        assert np.array_equal(g["kept"], r["kept"]) and compare(g, r, nd, g0, False) == 0
