@@ -76,6 +76,7 @@ template <> struct LogitVec<false> {
     {
         v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
     }
+    __device__ static __forceinline__ raw minus_inf() { return raw{-INFINITY, -INFINITY, -INFINITY, -INFINITY}; }
     __device__ static __forceinline__ float element(const void* base, size_t i)
     {
         return static_cast<const float*>(base)[i];
@@ -92,6 +93,7 @@ template <> struct LogitVec<true> {
         v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xFFFF0000u);
         v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xFFFF0000u);
     }
+    __device__ static __forceinline__ raw minus_inf() { return raw{0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u}; }
     __device__ static __forceinline__ float element(const void* base, size_t i)
     {
         return __uint_as_float((uint32_t)static_cast<const uint16_t*>(base)[i] << 16);
@@ -120,11 +122,15 @@ __global__ __launch_bounds__(256) void isd_row_stats_kernel(const void* __restri
     float z = 0.f;         // sum of 2^(l*k - ref_k(m, k))
     int argv = -1;         // index of the vector that holds the first occurrence of m
 
+    // One batch of UNROLL vectors per thread, all loads issued before the first use.  The last batch
+    // of a slice is ragged: its missing vectors read as -inf, which changes neither the maximum nor
+    // the sum (2^-inf = 0), so the tail keeps as many loads in flight as the body.
     int f = fbeg + tid;
-    for (; f + (UNROLL - 1) * 256 < fend; f += UNROLL * 256) {
+    auto batch = [&](const bool full) {
         raw_t v[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = __builtin_nontemporal_load(pv + f + u * 256);
+        for (int u = 0; u < UNROLL; ++u)
+            v[u] = (full || f + u * 256 < fend) ? __builtin_nontemporal_load(pv + f + u * 256) : LV::minus_inf();
         float newm = m;
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
@@ -139,6 +145,9 @@ __global__ __launch_bounds__(256) void isd_row_stats_kernel(const void* __restri
         float acc = z * rescale_k(m, r, k);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
+            // bf16: unpacked again from the loaded vector (two instructions per pair) rather than kept
+            // from the maximum loop, which would double the registers and cost two waves per SIMD
+            if constexpr (BF16) asm volatile("" : "+v"(v[u]));
             float e[N];
             LV::unpack(v[u], e);
 #pragma unroll
@@ -146,23 +155,9 @@ __global__ __launch_bounds__(256) void isd_row_stats_kernel(const void* __restri
         }
         z = acc;
         m = newm;
-    }
-    for (; f < fend; f += 256) {
-        const raw_t v = __builtin_nontemporal_load(pv + f);
-        float e[N];
-        LV::unpack(v, e);
-        float bm = e[0];
-#pragma unroll
-        for (int i = 1; i < N; ++i) bm = fmaxf(bm, e[i]);
-        float newm = m;
-        if (bm > newm) { newm = bm; argv = f; }
-        const float r = ref_k(newm, k);
-        float acc = z * rescale_k(m, r, k);
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc += fast_exp2(fmaf(e[i], k, -r));
-        z = acc;
-        m = newm;
-    }
+    };
+    for (; f + (UNROLL - 1) * 256 < fend; f += UNROLL * 256) batch(true);
+    if (f < fend) batch(false);
 
     // which component of that vector was first to reach m
     int arg = INT_MAX;

@@ -61,10 +61,6 @@ __device__ void sort_buffer_desc(unsigned long long* buf, int n)
 // the robust path: elements above the current threshold (the K-th largest key seen so far, 0
 // before K elements have been seen) are appended batch by batch; when the buffer cannot take the
 // next batch it is sorted and cut back to its K largest, which raises the threshold.
-template <bool BF16> __device__ __forceinline__ typename LogitVec<BF16>::raw vec_of_minus_inf();
-template <> __device__ __forceinline__ f32x4 vec_of_minus_inf<false>() { return f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY}; }
-template <> __device__ __forceinline__ u32x4 vec_of_minus_inf<true>() { return u32x4{0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u}; }
-
 template <int UNROLL, bool BF16>
 __global__ __launch_bounds__(256) void isd_row_topk_kernel(const void* __restrict__ logits, int V, int K,
                                                            unsigned long long* __restrict__ out_keys)
@@ -80,7 +76,7 @@ __global__ __launch_bounds__(256) void isd_row_topk_kernel(const void* __restric
     const int row = blockIdx.x, tid = threadIdx.x;
     const raw_t* __restrict__ pv = reinterpret_cast<const raw_t*>(static_cast<const char*>(logits) + (size_t)row * V * (16 / N));
     const int fend = V / N;
-    const raw_t none = vec_of_minus_inf<BF16>();
+    const raw_t none = LV::minus_inf();
     for (int t = tid; t < kBufCap; t += 256) buf[t] = 0ull;
     if (tid == 0) { s_count = 0; s_thr = 0ull; s_overflow = 0; s_first = -INFINITY; }
 
