@@ -208,3 +208,49 @@ def test_bf16_rows_in_adverse_order():
                                      sample_proposals=True)
         g, _ = call(logits, np.zeros((B, S - 1), np.int32), nd, g0, 2, 0, 1.0, 0.0, K, 1.0, True, bf16=True)
         assert np.array_equal(g["kept"], r["kept"]) and compare(g, r, nd, g0, False) == 0
+
+
+def test_full_size_launch_checked_on_the_first_sequences():
+    """The benchmark's shape (B = 256, S = 16, V = 151 936): both calls run on the whole batch, the oracle on the first
+    six sequences (row numbers, hence random streams, are those of the full batch)."""
+    B, S, V, nb = 256, 16, 151936, 6
+    gen = torch.Generator(device=DEV).manual_seed(20260411)
+    q_logits = torch.randn((B, S, V), generator=gen, device=DEV) * 3
+    logits = torch.randn((B, S, V), generator=gen, device=DEV) * 3
+    logits[:, :S - 1] = q_logits[:, 1:] + torch.randn((B, S - 1, V), generator=gen, device=DEV)
+    rng = np.random.default_rng(1)
+    n_draft = rng.integers(0, S, size=B).astype(np.int32)
+    greedy = (rng.random(B) < 0.2).astype(np.uint8)
+    zero = np.zeros(B, np.int32); none = np.zeros(B, np.uint8)
+    no_drafts = torch.zeros((B, S - 1), dtype=torch.int32, device=DEV)
+
+    def run(lg, drafts, nd, gr, seed, q_cand=None):
+        accept_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+        new_tokens = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+        probs = torch.full((B, S - 1), -7.0, device=DEV); dq = torch.full((B, S - 1), -7.0, device=DEV)
+        kept = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+        cand = torch.full((B, S, 64), -1, dtype=torch.int64, device=DEV)
+        idlm.idlm_isd_accept_filtered_q(lg, drafts, seed, accept_len, new_tokens, n_draft=dev(nd), top_k=50, top_p=0.95,
+                                        q_cand=q_cand, q_row=dev(np.ones(B, np.int32)) if q_cand is not None else None,
+                                        greedy=dev(gr), sample_proposals=True, draft_probs=probs, draft_q=dq, kept=kept,
+                                        cand_out=cand)
+        torch.cuda.synchronize()
+        out = dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs, draft_q=dq, kept=kept)
+        return {k: v[:nb].cpu().numpy() for k, v in out.items()}, cand
+
+    ga, record = run(q_logits, no_drafts, zero, none, 31)
+    qh = q_logits[:nb].cpu().numpy()
+    ra = oracle.accept_filtered_q(qh, np.zeros((nb, S - 1), np.int32), 31, n_draft=zero[:nb], top_k=50, top_p=0.95, greedy=none[:nb],
+                                  sample_proposals=True)
+    assert compare(ga, ra, zero[:nb], none[:nb], False) <= 1
+    # every sequence verifies what its own rows proposed in the first call (the first sequences: the oracle's draws)
+    drafts = torch.full((B, S - 1), -7, dtype=torch.int32, device=DEV)
+    al = torch.zeros(B, dtype=torch.int32, device=DEV); nt = torch.zeros((B, S), dtype=torch.int32, device=DEV)
+    idlm.idlm_isd_accept_filtered_q(q_logits, no_drafts, 31, al, nt, n_draft=0, top_k=50, top_p=0.95, sample_proposals=True,
+                                    workspace=torch.empty(idlm.idlm_isd_accept_filtered_workspace(B, S, V), dtype=torch.uint8, device=DEV))
+    drafts[:] = nt[:, 1:]
+    drafts[:nb] = torch.from_numpy(ra["new_tokens"][:, 1:].astype(np.int32)).to(DEV)
+    gb, _ = run(logits, drafts, n_draft, greedy, 32, q_cand=record)
+    rb = oracle.accept_filtered_q(logits[:nb].cpu().numpy(), drafts[:nb].cpu().numpy(), 32, n_draft=n_draft[:nb], top_k=50, top_p=0.95,
+                                  q_logits=qh, q_row=np.ones(nb, np.int32), greedy=greedy[:nb], sample_proposals=True)
+    assert compare(gb, rb, n_draft[:nb], greedy[:nb], True) <= 1
