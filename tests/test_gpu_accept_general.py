@@ -133,3 +133,44 @@ def test_large_ragged_vocabulary_and_single_row():
     idlm.idlm_isd_accept_general(t(l1), None, 3, al, nt, n_draft=t(z), temperature=0.9, workspace=ws)
     torch.cuda.synchronize()
     assert np.array_equal(nt.cpu().numpy(), r1["new_tokens"]) and (al.cpu().numpy() == 0).all()
+
+
+def test_full_size_launch_checked_on_the_first_sequences():
+    """The benchmark's shape (B = 256, S = 16, V = 151 936) with proposal distributions, temperature, relaxed threshold
+    and sampled proposals; the oracle runs the first five sequences (row numbers are those of the full batch)."""
+    B, S, V, nb, T, tau = 256, 16, 151936, 5, 0.9, 0.1
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    logits = torch.randn((B, S, V), generator=gen, device=DEV) * 3
+    q_logits = 0.6 * logits.flip(1) + 0.4 * 3 * torch.randn((B, S, V), generator=gen, device=DEV)
+    rng = np.random.default_rng(3)
+    n_draft = rng.integers(0, S, size=B).astype(np.int32)
+    q_row = np.array([rng.integers(0, S - d + 1) for d in n_draft], dtype=np.int32)
+    greedy = (rng.random(B) < 0.25).astype(np.uint8)
+    # drafts: the proposing row's arg-max everywhere, and for the sequences under test a draw from that row by numpy
+    rows = torch.from_numpy(q_row).to(DEV).long()[:, None] + torch.arange(S - 1, device=DEV)[None, :]
+    rows = rows.clamp(max=S - 1)
+    drafts = torch.gather(q_logits.argmax(-1), 1, rows).to(torch.int32)
+    lh, qh = logits[:nb].cpu().numpy(), q_logits[:nb].cpu().numpy()
+    for b in range(nb):
+        for j in range(n_draft[b]):
+            drafts[b, j] = int(rng.choice(V, p=softmax(qh[b, q_row[b] + j].astype(np.float64) / T)))
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    accept_len = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    new_tokens = torch.full((B, S), -7, dtype=torch.int32, device=DEV)
+    probs = torch.full((B, S - 1), -7.0, device=DEV); dq = torch.full((B, S - 1), -7.0, device=DEV)
+    lse = torch.full((B, S), -7.0, device=DEV)
+    ws = torch.empty(idlm.idlm_isd_accept_general_workspace(B, S, V), dtype=torch.uint8, device=DEV)
+    idlm.idlm_isd_accept_general(logits, drafts, 123, accept_len, new_tokens, n_draft=t(n_draft), q_logits=q_logits, q_row=t(q_row),
+                                 greedy=t(greedy), rng_offset=6, temperature=T, tau=tau, sample_proposals=True, draft_probs=probs,
+                                 draft_q=dq, row_lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    g = dict(accept_len=accept_len[:nb].cpu().numpy(), new_tokens=new_tokens[:nb].cpu().numpy(), draft_probs=probs[:nb].cpu().numpy(),
+             draft_q=dq[:nb].cpu().numpy(), row_lse=lse[:nb].cpu().numpy())
+    r = oracle.accept_general(lh, drafts[:nb].cpu().numpy(), 123, n_draft=n_draft[:nb], q_logits=qh, q_row=q_row[:nb], greedy=greedy[:nb],
+                              rng_offset=6, temperature=T, tau=tau, sample_proposals=True)
+    assert compare(g, r, n_draft[:nb], greedy[:nb], True) <= 1
+    # every sequence got outputs of the right form
+    al = accept_len.cpu().numpy(); nt = new_tokens.cpu().numpy()
+    assert (al >= 0).all() and (al <= n_draft).all()
+    for b in range(B):
+        assert (nt[b, :al[b] + 1] >= 0).all() and (nt[b, al[b] + 1:n_draft[b] + 1] == -1).all() and (nt[b, n_draft[b] + 1:] >= 0).all()
