@@ -196,6 +196,21 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # what the last timed step accepted on these synthetic inputs (bookkeeping on the outputs): the
+    # introspective acceptance rate is the mean accept probability of the verified drafts, here p(draft)
+    acceptance = None
+    if S > 1:
+        nd_f = acc.n_draft.clamp(max=S - 1).float()
+        verified = torch.arange(S - 1, device=dev)[None, :] < acc.n_draft[:, None]
+        stochastic = (acc.greedy == 0) if acc.greedy is not None else torch.ones(B, dtype=torch.bool, device=dev)
+        acceptance = {
+            "mean_drafts_per_sequence": float(nd_f.mean().item()),
+            "mean_accept_len": float(accept_len.float().mean().item()),
+            "tokens_finalised_per_sequence_per_step": float((accept_len.float() + 1).mean().item()),
+            "introspective_acceptance_rate_mean_p_draft": float(draft_probs[verified].mean().item()) if bool(verified.any()) else None,
+            "stochastic_share": float(stochastic.float().mean().item()),
+        }
+
     def avg(which, a, b):
         return sum(hev.elapsed_ms(e[which][a], e[which][b]) for e in events) / len(events)
 
@@ -458,6 +473,7 @@ def main():
         "between_steps": loop_kernels,
         "launch_modes": launch_modes,
         "k_page_layouts": k_layouts,
+        "acceptance": acceptance,
         "accept_general": gen,
         "accept_bf16_logits": bf16_acc,
         "gated_lora_linear": lora,
