@@ -407,8 +407,9 @@ int idlm_isd_commit(const int32_t* accept_len, const int32_t* new_tokens, int32_
  *          strides of S rows is a MASK position iff j > n_draft[b] (int32 [T/S], clamped to
  *          [0,S-1]; T % S == 0), the row order of idlm_isd_attention / idlm_isd_accept.
  * h        bf16 [T,d_out] out.
- * tile_tokens  0 = choose (the largest token tile that still gives every compute unit a
- *          workgroup), or 64 / 128 / 256 to force it (tuning, tests).
+ * tile_tokens  0 = choose (with k_splits = 0: the pair that a small cost model of the launch -
+ *          rounds of workgroups over the compute units, cost of a reduction step per tile
+ *          size, traffic of the partial sums - rates cheapest), or 64 / 128 / 256 to force it.
  * k_splits     0 = choose, or 1..16: the reduction over d_in is cut into this many parts, one
  *          workgroup each, summed in a fixed order by a second kernel (few tokens: more
  *          workgroups for the same weight traffic).  Results do not depend on the number of

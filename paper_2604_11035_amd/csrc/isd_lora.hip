@@ -375,19 +375,45 @@ int pick_splits(int64_t tiles, int steps, int max_splits)
     return z < 1 ? 1 : z;
 }
 
+// Estimated time of the projection for a token tile and a number of reduction parts, in microseconds
+// as measured on an MI355X (only the order of the candidates matters).  One workgroup runs per compute
+// unit at a time, so the launch takes ceil(workgroups / units) rounds; a 64-wide reduction step costs a
+// 64 / 128 / 256-token tile about 0.66 / 1.0 / 1.5 us; partial sums are written and read once more by
+// the second kernel.
+static double projection_cost(int64_t T, int64_t d_out, int steps, int lora_steps, int bm, int splits)
+{
+    const int64_t tiles = ((T + bm - 1) / bm) * ((d_out + 255) / 256);
+    const int64_t rounds = (tiles * splits + kUnits - 1) / kUnits;
+    const double step_us = bm == 64 ? 0.66 : bm == 128 ? 1.0 : 1.5;
+    const int per_part = (steps + splits - 1) / splits + lora_steps;      // the adapter's columns go to the last part
+    double us = 4.0 + (double)rounds * per_part * step_us;
+    if (splits > 1) us += 3.0 + (double)splits * (double)T * (double)d_out * 4.0 / 4.0e6;
+    return us;
+}
+
 LoraPlan make_lora_plan(int32_t T, int32_t d_in, int32_t d_out, int32_t r, int32_t tile_tokens, int32_t k_splits)
 {
     LoraPlan pl{};
-    const int64_t tn = (d_out + 255) / 256;
-    int bm = tile_tokens;
-    if (bm == 0) {   // the largest token tile that still gives every compute unit a workgroup, else the
-        bm = 64;     // smallest that holds all tokens
-        if (T > 64) bm = 128;
-        if ((int64_t)((T + 255) / 256) * tn >= kUnits) bm = 256;
+    const int steps = d_in / kBK;
+    // token tile and reduction parts: what was asked for, else the cheapest of the candidates
+    int bm = tile_tokens, best_splits = k_splits;
+    if (tile_tokens == 0 || k_splits == 0) {
+        double best = 0.0;
+        bool have = false;
+        for (int cb = 64; cb <= 256; cb *= 2) {
+            if (tile_tokens != 0 && cb != tile_tokens) continue;
+            if (tile_tokens == 0 && cb > 64 && cb / 2 >= T) continue;          // a tile twice the batch computes padding only
+            for (int cs = 1; cs <= (k_splits ? 16 : 8); ++cs) {
+                if (k_splits != 0 && cs != k_splits) continue;
+                if (k_splits == 0 && cs > 1 && steps / cs < 4) break;          // at least four steps per part
+                const double c = projection_cost(T, d_out, steps, r / kBK, cb, cs);
+                if (!have || c < best) { best = c; bm = cb; best_splits = cs; have = true; }
+            }
+        }
+        if (!have) { bm = tile_tokens ? tile_tokens : 64; best_splits = k_splits ? k_splits : 1; }
     }
     pl.bm = bm;
-    const int64_t tiles = (int64_t)((T + bm - 1) / bm) * tn;
-    pl.splits = k_splits > 0 ? k_splits : pick_splits(tiles, d_in / kBK, 8);
+    pl.splits = best_splits;
     if (pl.splits > d_in / kBK) pl.splits = d_in / kBK;
     pl.shrink_splits = 1;
     if (r > 0) {
