@@ -255,6 +255,16 @@ def test_filtered_q_accept_rejects_bad_arguments(kw, code):
     assert _filtered_q(B=0) == 0
 
 
+def test_rng_dump_rejects_bad_arguments():
+    f = idlm.lib().idlm_isd_rng_dump
+    assert f(1, 0, 1, 0, 0, 64, None, None, None) == 0                 # no rows: nothing to do
+    assert f(1, 0, 1, 0, 2, 64, None, None, None) == -1                # no output at all
+    assert f(1, 0, 1, 0, 65536, 64, FAKE, None, None) == -2
+    assert f(1, 0, 1, -1, 2, 64, FAKE, None, None) == -2 and f(1, 0, -1, 0, 2, 64, FAKE, None, None) == -2
+    assert f(1, 0, 1, 0, 2, 0, FAKE, None, None) == -2
+    assert f(1, 0, 1, 2**31 - 1, 2, 64, FAKE, None, None) == -2        # row numbers must stay below 2^31
+
+
 def _lora(**kw):
     a = dict(x=FAKE, W=FAKE, A=FAKE, Bm=FAKE, gate=FAKE, nd=None, S=1, h=FAKE, T=32, d_in=256, d_out=512, r=128, tile=0,
              splits=0, ws=None, ws_bytes=0, stream=None)
