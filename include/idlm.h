@@ -245,6 +245,7 @@ int idlm_isd_rng_dump(uint64_t rng_seed, uint32_t rng_offset, int32_t stream_tag
  *              row_lse output of the call that processed q_logits at the same T.  NULL with
  *              q_logits given costs one more streaming pass over q_logits.
  * temperature  T > 0.  tau >= 0.
+ *              q_j(x_j) = 0: the draft is accepted iff p_j(x_j) > 0 (p = q = 0 is rejected).
  * sample_proposals  non-zero: rows after the drafts propose argmax_i(l_i/T + Gumbel noise of
  *              random stream 2) instead of the arg-max (greedy sequences always use the arg-max).
  * fresh token  after a rejection: argmax_i [ln(p(i) - q(i)) + g_i] over i with p(i) > q(i)

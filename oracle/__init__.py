@@ -48,8 +48,6 @@ def lib() -> C.CDLL:
                                         C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]
         L.isd_oracle_accept.restype = C.c_int
-        L.isd_oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.isd_oracle_row_stats.restype = C.c_int
         L.isd_oracle_num_threads.restype = C.c_int
         L.isd_oracle_rng_dump.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.isd_oracle_rng_dump.restype = None
@@ -190,17 +188,6 @@ def accept(logits, draft_tokens, rng_seed, *, n_draft, greedy=None, rng_offset=0
         raise ValueError("isd_oracle_accept failed: %d" % rc)
     return dict(accept_len=accept_len, new_tokens=new_tokens, draft_probs=probs,
                 accept_margin=margin, sample_gap=gap, runner_up=runner)
-
-
-def row_stats(row):
-    row = np.ascontiguousarray(row, dtype=np.float32)
-    m = C.c_double()
-    z = C.c_double()
-    a = C.c_int32()
-    rc = lib().isd_oracle_row_stats(_ptr(row), row.size, C.byref(m), C.byref(z), C.byref(a))
-    if rc != 0:
-        raise ValueError("isd_oracle_row_stats failed")
-    return m.value, z.value, a.value
 
 
 def kv_append(k_new, v_new, k_cache, v_cache, block_table, ctx_lens, S, *, Hkv, D, P, strides=None):

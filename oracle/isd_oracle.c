@@ -387,7 +387,7 @@ static void row_lse(const float* l, int V, double T, double* lse, int32_t* arg)
  * For sequence b with D drafts:
  *   1. every row j: lse_j of l_j/T, arg-max a_j.
  *   2. j < D: p_j = exp(l_j[x_j]/T - lse_j); q_j likewise from the q row (1 for point mass).
- *   3. accept_j: greedy ? x_j == a_j : u_{b,j} < min(1, (1+tau) p_j/q_j)   (q_j = 0: accepted).
+ *   3. accept_j: greedy ? x_j == a_j : u_{b,j} < min(1, (1+tau) p_j/q_j)   (q_j = 0: accepted iff p_j > 0).
  *   4. r = accepted prefix.
  *   5. fresh token of row r: greedy: a_r.  Otherwise, after a rejection (r < D):
  *        argmax_i [ln(p_r(i) - q_r(i)) + g_{b,r,i}] over i with p_r(i) > q_r(i)
@@ -462,7 +462,9 @@ int isd_oracle_accept_general(const float* logits, const int32_t* draft_tokens, 
                 ok = (x == a[j]);
             } else {
                 const double u = isd_oracle_accept_uniform(rng_seed, rng_offset, (uint32_t)(b * S + j));
-                double thr = (q > 0.0) ? (1.0 + tau) * p / q : INFINITY;
+                /* q = 0: p/q is infinite for p > 0 (accepted); p = q = 0 is rejected, so that no token
+                 * of zero anchor probability is ever finalised (Sec. 3.2: the output follows p) */
+                double thr = (q > 0.0) ? (1.0 + tau) * p / q : (p > 0.0 ? INFINITY : 0.0);
                 if (thr > 1.0) thr = 1.0;
                 ok = (u < thr);
                 if (accept_margin) accept_margin[(int64_t)b * ncol + j] = fabs(u - thr);
@@ -951,22 +953,6 @@ int isd_oracle_segment_gate(const int32_t* n_draft, uint8_t* gate, int32_t B, in
         if (nd > S - 1) nd = S - 1;
         for (int j = 0; j < S; ++j) gate[(int64_t)b * S + j] = (uint8_t)(j > nd);
     }
-    return ORACLE_OK;
-}
-
-/* Row statistics alone (m, Z, arg-max) for spot checks of very large inputs. */
-int isd_oracle_row_stats(const float* row, int32_t V, double* m_out, double* z_out, int32_t* arg_out)
-{
-    if (!row || V < 1) return ORACLE_ERR_ARG;
-    double mx = -INFINITY;
-    int arg = 0;
-    for (int i = 0; i < V; ++i)
-        if ((double)row[i] > mx) { mx = (double)row[i]; arg = i; }
-    double z = 0.0;
-    for (int i = 0; i < V; ++i) z += exp((double)row[i] - mx);
-    if (m_out) *m_out = mx;
-    if (z_out) *z_out = z;
-    if (arg_out) *arg_out = arg;
     return ORACLE_OK;
 }
 

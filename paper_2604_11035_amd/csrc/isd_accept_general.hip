@@ -107,7 +107,9 @@ __global__ __launch_bounds__(64) void isd_accept_general_chain_kernel(const Gene
                 ok = (x == a);
             } else {
                 const uint4 w = philox4x32_10(make_uint4(0u, (uint32_t)row, 0u, p.rng_offset), p.key);
-                const float thr = qv > 0.f ? fminf(1.f, p.one_plus_tau * pr / qv) : 1.f;
+                // q(x) = 0: a draft the proposer could not have drawn passes iff the anchor gives it any mass (p/q = inf),
+                // and fails when the anchor gives it none (0/0: the output must stay on the anchor distribution)
+                const float thr = qv > 0.f ? fminf(1.f, p.one_plus_tau * pr / qv) : (pr > 0.f ? 1.f : 0.f);
                 ok = unit_uniform(w.x) < thr;
             }
         }

@@ -114,6 +114,31 @@ def test_general_proposals_match_the_oracle(T, tau, samp):
     assert rej.sum() >= 5 and ((r["accept_len"] == n_draft) & (n_draft > 0)).sum() >= 5      # both branches exercised
 
 
+def test_drafts_outside_the_proposers_support_and_invalid_draft_ids():
+    """q(x) = 0: accepted iff the anchor gives x any mass; p(x) = q(x) = 0 is rejected like a point-mass draft of
+    probability zero, and so is a draft id outside the vocabulary (which the oracle refuses to take, so the
+    expected outputs for it are written out here)."""
+    rng = np.random.default_rng(4)
+    B, S, V, T = 32, 4, 2048, 1.0
+    logits, q_logits, q_row, drafts, n_draft, greedy = make_case(rng, B, S, V, T, 0.3)
+    n_draft[:] = 2; q_row[:] = 1; greedy[:] = 0
+    drafts[:, 0] = rng.integers(0, V, size=B)
+    for b in range(B):
+        q_logits[b, 1, drafts[b, 0]] = -np.inf            # the proposer of draft 0 could not have drawn it
+        if b % 2:
+            logits[b, 0, drafts[b, 0]] = -np.inf          # ... and the anchor gives it no mass either
+    r = oracle.accept_general(logits, drafts, 9, n_draft=n_draft, q_logits=q_logits, q_row=q_row, greedy=greedy)
+    assert (r["accept_len"][1::2] == 0).all() and (r["accept_len"][0::2] >= 1).all()
+    g = run_gpu(logits, drafts, n_draft, greedy, 9, 0, T, 0.0, False, q_logits, q_row)
+    assert compare(g, r, n_draft, greedy, True) <= 1
+    assert (g["draft_q"][:, 0] == 0).all() and (g["draft_probs"][1::2, 0] == 0).all()
+    # invalid ids: p = q = 0, rejected at once, the resample excludes nothing that exists
+    bad = drafts.copy(); bad[:, 0] = np.where(np.arange(B) % 2, V, -1)
+    gb = run_gpu(logits, bad, n_draft, greedy, 9, 0, T, 0.0, False, q_logits, q_row)
+    assert (gb["accept_len"] == 0).all() and (gb["draft_probs"][:, 0] == 0).all() and (gb["draft_q"][:, 0] == 0).all()
+    assert ((gb["new_tokens"][:, 0] >= 0) & (gb["new_tokens"][:, 0] < V)).all() and (gb["new_tokens"][:, 1:3] == -1).all()
+
+
 def test_large_ragged_vocabulary_and_single_row():
     rng = np.random.default_rng(12)
     B, S, V, T = 6, 4, 151936, 1.2

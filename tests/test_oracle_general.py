@@ -125,6 +125,27 @@ def test_greedy_ignores_proposal_distribution_threshold_and_temperature():
     assert np.array_equal(a["accept_len"], want)
 
 
+def test_draft_outside_the_proposers_support():
+    """q(x) = 0 (the proposer could not have drawn x): min(1, p/q) of Alg. 1 is 1 when the anchor gives x any
+    mass, and the draft is rejected when the anchor gives it none (0/0), so that a token of zero anchor
+    probability is never finalised (Sec. 3.2: outputs follow the anchor distribution)."""
+    V, B = 8, 64
+    ninf = np.float32(-np.inf)
+    lp = np.zeros((B, 2, V), np.float32)
+    lp[:, 0] = np.linspace(-1, 1, V)            # a non-uniform anchor, so that {p > q} is not empty
+    lq = np.zeros((B, 2, V), np.float32)
+    lq[:, 1, 3] = ninf                          # q(3) = 0 for the draft of row 0
+    drafts = np.full((B, 1), 3, np.int32)
+    q_row = np.ones(B, np.int32)
+    r = oracle.accept_general(lp, drafts, 5, n_draft=1, q_logits=lq, q_row=q_row)
+    assert (r["accept_len"] == 1).all() and (r["new_tokens"][:, 0] == 3).all()      # p(3) > 0: always accepted
+    lp[:, 0, 3] = ninf                          # now p(3) = 0 as well
+    r = oracle.accept_general(lp, drafts, 5, n_draft=1, q_logits=lq, q_row=q_row)
+    assert (r["accept_len"] == 0).all() and (r["draft_probs"][:, 0] == 0).all() and (r["draft_q"][:, 0] == 0).all()
+    assert (r["new_tokens"][:, 0] != 3).all()   # the resample comes from {p > q}, which cannot hold 3
+    assert set(np.unique(r["new_tokens"][:, 0])) == {5, 6, 7}   # p > q = 1/7 only for the three largest logits
+
+
 def test_general_acceptance_refuses_malformed_input():
     l = np.zeros((1, 3, 8), np.float32)
     d = np.zeros((1, 2), np.int32)
