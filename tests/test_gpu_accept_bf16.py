@@ -40,7 +40,7 @@ def test_small_model(mode):
     h = _helpers()
     inp = _mk("small", mode=mode, draft_hit=0.6 if mode == "greedy" else 0.8)
     got, ref = h.gpu_accept(inp, bf16=True), h.oracle_accept(inp, bf16=True)
-    h.compare_accept(got, ref, inp.cfg.drafts, strict=False)
+    assert h.compare_accept(got, ref, inp.cfg.drafts, strict=False) <= 1
     assert 0 < ref["accept_len"].mean() < inp.cfg.drafts
 
 
@@ -84,7 +84,7 @@ def test_ragged_vocabulary_and_small_strides(V, S):
     gr = rng.integers(0, 2, size=B)
     inp = _custom(logits, drafts, nd, gr, seed=1000 + V + S)
     got, ref = h.gpu_accept(inp, bf16=True), h.oracle_accept(inp, bf16=True)
-    h.compare_accept(got, ref, nd, strict=False)
+    assert h.compare_accept(got, ref, nd, strict=False) <= 1
 
 
 def test_minus_infinity_and_point_masses():
@@ -101,7 +101,7 @@ def test_minus_infinity_and_point_masses():
     for gr in (1, 0):
         inp = _custom(logits, drafts, 3, gr)
         got, ref = h.gpu_accept(inp, bf16=True), h.oracle_accept(inp, bf16=True)
-        h.compare_accept(got, ref, 3, strict=False)
+        assert h.compare_accept(got, ref, 3, strict=False) <= 1
         assert got["accept_len"][1] == 3 and (got["new_tokens"][1] == 77).all()
         assert got["accept_len"][2] == 0 and got["new_tokens"][2, 0] in (5, 2000)
         assert got["accept_len"][3] == 3
