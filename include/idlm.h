@@ -188,6 +188,30 @@ int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
 
 /*
+ * idlm_isd_accept_static - idlm_isd_accept for callers that cannot allocate or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * arguments, results (bit for bit) and error behaviour as idlm_isd_accept, without `workspace`:
+ * the scratch memory is a fixed array of idlm_isd_accept_static_max_bytes() bytes (1 MiB) in the
+ * library's device image, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing (no hipMalloc / hipFree, no allocating library routine) and does not synchronise.
+ * Limit: idlm_isd_accept_workspace(B,S,V) must not exceed idlm_isd_accept_static_max_bytes()
+ * (about 60 000 logit rows per call; the benchmark's B=256, S=16 needs 72 KB); beyond it the call
+ * returns IDLM_ERR_WORKSPACE and launches nothing.
+ * All calls on one GPU share that GPU's array: two calls whose kernels can overlap on one GPU
+ * (different streams without an ordering event, several host threads) race on it - order them,
+ * or use idlm_isd_accept with separate workspaces.  The array keeps the last call's contents;
+ * every word a call reads it has written before, so nothing needs clearing between calls.
+ */
+int idlm_isd_accept_static(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                           int32_t* accept_len, int32_t* new_tokens,
+                           int32_t B, int32_t S, int32_t V,
+                           int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
+                           uint32_t rng_offset, float* draft_probs, void* stream);
+
+/* Size in bytes of the fixed scratch array idlm_isd_accept_static uses (host-only). */
+size_t idlm_isd_accept_static_max_bytes(void);
+
+/*
  * idlm_isd_accept_bf16 - the same acceptance (Alg. 1, introspection loop; Sec. 3.3 (3)) over
  * logits stored as bf16, which halves the bytes the pass has to read.  Every logit widens
  * exactly to fp32 and all arithmetic after the load is that of idlm_isd_accept, so the results

@@ -47,6 +47,10 @@ def lib() -> C.CDLL:
         L.idlm_isd_accept.restype = C.c_int
         L.idlm_isd_accept_ev.argtypes = L.idlm_isd_accept.argtypes + [vp]
         L.idlm_isd_accept_ev.restype = C.c_int
+        L.idlm_isd_accept_static.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32, vp, vp]
+        L.idlm_isd_accept_static.restype = C.c_int
+        L.idlm_isd_accept_static_max_bytes.argtypes = []
+        L.idlm_isd_accept_static_max_bytes.restype = C.c_size_t
         L.idlm_isd_accept_bf16.argtypes = L.idlm_isd_accept.argtypes
         L.idlm_isd_accept_bf16.restype = C.c_int
         L.idlm_isd_accept_bf16_ev.argtypes = L.idlm_isd_accept_ev.argtypes
@@ -179,6 +183,19 @@ def idlm_isd_accept_bf16(logits, draft_tokens, rng_seed, accept_len, new_tokens,
     return _accept(lib().idlm_isd_accept_bf16_ev, "idlm_isd_accept_bf16", torch.bfloat16, logits, draft_tokens,
                    rng_seed, accept_len, new_tokens, n_draft, greedy, rng_offset, draft_probs, workspace, stream,
                    events)
+
+
+def idlm_isd_accept_static_max_bytes() -> int:
+    return int(lib().idlm_isd_accept_static_max_bytes())
+
+
+def idlm_isd_accept_static(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
+                           rng_offset=0, draft_probs=None, stream=None):
+    """idlm_isd_accept without a workspace argument: the scratch is a fixed array inside the library (see idlm.h)."""
+    def fn(*a):
+        return lib().idlm_isd_accept_static(*a[:13], a[15])      # no workspace, no workspace size, no events
+    return _accept(fn, "idlm_isd_accept_static", torch.float32, logits, draft_tokens, rng_seed, accept_len, new_tokens,
+                   n_draft, greedy, rng_offset, draft_probs, None, stream, None)
 
 
 def _accept(fn, name, dtype, logits, draft_tokens, rng_seed, accept_len, new_tokens, n_draft, greedy,

@@ -8,6 +8,7 @@
 //   4. decode of the winning keys into new_tokens.
 // HBM-bound: the algorithmic traffic is one read of the logits (4*V bytes per row).
 #include "isd_accept_common.h"
+#include <mutex>
 
 namespace idlm {
 
@@ -316,4 +317,61 @@ extern "C" int idlm_isd_accept_bf16(const uint16_t* logits, const int32_t* draft
     return accept_impl<true>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V,
                              n_draft_uniform, n_draft, greedy, rng_offset, draft_probs, workspace,
                              workspace_bytes, stream, nullptr);
+}
+
+// ---- the same call for callers that cannot allocate -------------------------------------------
+// The workspace of idlm_isd_accept (slice statistics, one arg-max key and one chain record per
+// sequence) lives in a fixed array in device memory instead of a caller's buffer.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.
+
+namespace idlm {
+
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+constexpr int kMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// In host code `scratch` is only a handle for the runtime, not an address a kernel could use: the
+// array's device address on the current device is asked for once per device and kept.
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void** ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return IDLM_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return IDLM_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return IDLM_OK;
+}
+
+}  // namespace idlm
+
+extern "C" size_t idlm_isd_accept_static_max_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int idlm_isd_accept_static(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
+                                      int32_t* accept_len, int32_t* new_tokens, int32_t B, int32_t S,
+                                      int32_t V, int32_t n_draft_uniform, const int32_t* n_draft,
+                                      const uint8_t* greedy, uint32_t rng_offset, float* draft_probs,
+                                      void* stream)
+{
+    // shapes first, so that a rejected shape is reported as such and an oversized one as IDLM_ERR_WORKSPACE
+    if (B < 0 || S < 1 || S > 64 || V < 4 || (V & 3) || (int64_t)B * S >= INT32_MAX) return IDLM_ERR_SHAPE;
+    if (B == 0) return IDLM_OK;
+    if (idlm_isd_accept_workspace(B, S, V) > kStaticScratchBytes) return IDLM_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != IDLM_OK) return rc;
+    // every word of the scratch that a kernel of the call reads is written earlier in the same call (slice
+    // statistics by the streaming pass, keys and chain records by the chain kernel), so nothing has to be cleared
+    return accept_impl<false>(logits, draft_tokens, rng_seed, accept_len, new_tokens, B, S, V, n_draft_uniform,
+                              n_draft, greedy, rng_offset, draft_probs, ws, kStaticScratchBytes, stream, nullptr);
 }

@@ -120,6 +120,19 @@ def test_accept_empty_batch_and_single_row_without_drafts():
     assert _accept(S=1, ndu=0, drafts=None) == -5
 
 
+def test_accept_static_checks_shapes_and_its_fixed_limit_before_touching_a_device():
+    L = idlm.lib()
+    cap = idlm.idlm_isd_accept_static_max_bytes()
+    assert cap == 1 << 20 and idlm.idlm_isd_accept_workspace(256, 16, 151936) < cap
+
+    def call(B=2, S=4, V=1024, ndu=1):
+        return L.idlm_isd_accept_static(FAKE, FAKE, 7, FAKE, FAKE, B, S, V, ndu, None, None, 0, None, None)
+    assert call(B=0) == 0
+    assert call(S=0) == -2 and call(S=65) == -2 and call(V=1023) == -2 and call(B=-1) == -2
+    assert idlm.idlm_isd_accept_workspace(8192, 16, 1024) > cap
+    assert call(B=8192, S=16) == -5                      # beyond the fixed array: refused, nothing launched
+
+
 def test_stream_helpers_validate():
     L = idlm.lib()
     assert L.idlm_stream_copy(None, FAKE, 16, None) == -1
