@@ -19,11 +19,21 @@ _LIB = _DIR / "libisd_oracle.so"
 _lib = None
 
 
+# ISD_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (CPU only; the process that loads it must have libasan preloaded,
+# see tests/test_oracle_sanitized.py).
+_SANITIZE = os.environ.get("ISD_ORACLE_SANITIZE", "") not in ("", "0")
+if _SANITIZE:
+    _LIB = _DIR / "libisd_oracle_san.so"
+
+
 def build(force: bool = False) -> Path:
-    """Compile the oracle with gcc (-O2, OpenMP)."""
+    """Compile the oracle with gcc (-O2, OpenMP; or -O1 with the sanitizers)."""
     if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
         tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=undefined"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *opt, "-std=c11", "-fopenmp", "-shared", "-fPIC",
                                "-o", str(tmp), str(_SRC), "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
