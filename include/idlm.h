@@ -97,10 +97,10 @@ enum {
  *             arithmetic, for correctness rather than speed: IDLM_DTYPE_F32 with D in {64,128} and
  *             IDLM_DTYPE_BF16 with D = 64.
  * num_workgroups  size of the persistent grid that shares the batch's 32-token tiles evenly;
- *             0 = one workgroup per compute unit of the current device, fewer when B and the
+ *             0 = one workgroup per compute unit of the current device (at most 256), fewer when B and the
  *             width of the block table bound the work to a few tiles per wavefront (the setting to use);
  *             1..1024 forces a grid (testing, or leaving compute units to other streams).
- * workspace   at least idlm_isd_attention_workspace(...) bytes, 256-byte aligned (MFMA path:
+ * workspace   at least idlm_isd_attention_workspace(..., num_workgroups) bytes, 256-byte aligned (MFMA path:
  *             partial results of the sequences that a slice boundary cuts;
  *             the plain path needs none and accepts NULL).
  * Supported: P = 16, 1 <= S <= 32, 0 <= B <= 65535 (B = 0 is a no-op), B*max_pages_per_seq < 2^31.
@@ -113,26 +113,13 @@ int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
                        float scale, int32_t dtype, int32_t num_workgroups,
                        void* workspace, size_t workspace_bytes, void* stream);
 
-/*
- * Same call with timing hooks: `events`, when not NULL, is a HOST array of three hipEvent_t
- * (as void*) created by the caller; they are recorded on `stream` before the main kernel,
- * between the main kernel and the kernel that joins partial results, and after the latter, so that a
- * benchmark can time each kernel of the call without a profiler.  events == NULL is exactly
- * idlm_isd_attention.  For the fp32 path events[1] and events[2] are both recorded after its
- * single kernel.
- */
-int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
-                          const int32_t* block_table, const int32_t* ctx_lens, int32_t S, void* out,
-                          int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
-                          int32_t num_pages, int32_t max_pages_per_seq,
-                          int64_t page_stride, int64_t head_stride, int64_t token_stride,
-                          float scale, int32_t dtype, int32_t num_workgroups,
-                          void* workspace, size_t workspace_bytes, void* stream, void* const* events);
-
-/* Bytes of workspace idlm_isd_attention needs for these shapes (host-only, no GPU needed).
- * Returns 0 for shapes that are rejected anyway. */
+/* Bytes of workspace idlm_isd_attention needs for these shapes and this num_workgroups (the value
+ * that will be passed to the call; 0 = the library's own choice, at most 256 workgroups): two
+ * partial-result slots per wavefront of the grid, 35 MB for the default grid at S*G >= 33 query
+ * rows per KV head.  Host-only, no GPU needed.  Returns 0 for shapes that are rejected anyway. */
 size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
-                                    int32_t P, int32_t max_pages_per_seq, int32_t dtype);
+                                    int32_t P, int32_t max_pages_per_seq, int32_t dtype,
+                                    int32_t num_workgroups);
 
 /*
  * idlm_isd_accept - introspective acceptance over the step's logits.
@@ -175,15 +162,6 @@ int idlm_isd_accept(const float* logits, const int32_t* draft_tokens, uint64_t r
                     uint32_t rng_offset, float* draft_probs,
                     void* workspace, size_t workspace_bytes, void* stream);
 
-/* Same call with timing hooks (see idlm_isd_attention_ev): three events, recorded before the
- * row-statistics kernel, between it and the accept/sample kernel, and after the latter. */
-int idlm_isd_accept_ev(const float* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                       int32_t* accept_len, int32_t* new_tokens,
-                       int32_t B, int32_t S, int32_t V,
-                       int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
-                       uint32_t rng_offset, float* draft_probs,
-                       void* workspace, size_t workspace_bytes, void* stream, void* const* events);
-
 /* Bytes of workspace idlm_isd_accept needs (host-only). Returns 0 for rejected shapes. */
 size_t idlm_isd_accept_workspace(int32_t B, int32_t S, int32_t V);
 
@@ -220,7 +198,7 @@ size_t idlm_isd_accept_static_max_bytes(void);
  *
  * logits  bf16 (raw 16-bit patterns) [B,S,V] contiguous, 16-byte aligned; V % 8 == 0, V >= 8.
  * All other arguments, the workspace size (idlm_isd_accept_workspace) and the error behaviour
- * are those of idlm_isd_accept; the _ev form records the same three events.
+ * are those of idlm_isd_accept.
  */
 int idlm_isd_accept_bf16(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
                          int32_t* accept_len, int32_t* new_tokens,
@@ -228,27 +206,6 @@ int idlm_isd_accept_bf16(const uint16_t* logits, const int32_t* draft_tokens, ui
                          int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
                          uint32_t rng_offset, float* draft_probs,
                          void* workspace, size_t workspace_bytes, void* stream);
-
-int idlm_isd_accept_bf16_ev(const uint16_t* logits, const int32_t* draft_tokens, uint64_t rng_seed,
-                            int32_t* accept_len, int32_t* new_tokens,
-                            int32_t B, int32_t S, int32_t V,
-                            int32_t n_draft_uniform, const int32_t* n_draft, const uint8_t* greedy,
-                            uint32_t rng_offset, float* draft_probs,
-                            void* workspace, size_t workspace_bytes, void* stream, void* const* events);
-
-/*
- * idlm_isd_rng_dump - the random numbers of the acceptance pass, written out (a check, not part
- * of the step): for r < n_rows and i < V, the uniform u = (2 (x >> 9) + 1) 2^-24 and the Gumbel
- * noise g = -ln(-ln u) that vocabulary element i of logit row row0 + r draws, x being word i & 3
- * of Philox4x32-10 at counter (i >> 2, row0 + r, stream_tag, rng_offset) with key (rng_seed low,
- * high) - the generator Sec. 3.3 (3) leaves open ("Gumbel-max"); stream tags: 0 accept-test
- * uniform (element 0 of the row), 1 Gumbel noise of the fresh token, 2 of sampled proposals.
- * uniforms, gumbels  fp32 [n_rows, V] device, out; either may be NULL (not both).
- * The uniforms are exact (24-bit numerators); the noise is evaluated in single precision.
- * n_rows <= 65535.  Asynchronous on `stream`; errors as the other calls.
- */
-int idlm_isd_rng_dump(uint64_t rng_seed, uint32_t rng_offset, int32_t stream_tag, int32_t row0, int32_t n_rows,
-                      int32_t V, float* uniforms, float* gumbels, void* stream);
 
 /*
  * idlm_isd_accept_general - acceptance with general proposal distributions, sampling
@@ -481,18 +438,6 @@ const char* idlm_strerror(int code);
 
 /* IDLM_VERSION of the loaded library. */
 int idlm_version(void);
-
-/*
- * Measurement aid: copies n_bytes from src to dst with 16-byte loads and stores (n_bytes a
- * multiple of 16, both 16-byte aligned).  Used to calibrate hardware byte counters and to
- * measure the streaming bandwidth actually reachable on the device.  Same stream / error
- * conventions as above.
- */
-int idlm_stream_copy(const void* src, void* dst, size_t n_bytes, void* stream);
-
-/* Measurement aid: reads n_bytes (multiple of 16, 16-byte aligned) and writes one 4-byte
- * checksum word to *sink (device pointer): a read-only streaming pass. */
-int idlm_stream_read(const void* src, size_t n_bytes, uint32_t* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -40,7 +40,7 @@ def lib() -> C.CDLL:
         L.idlm_isd_attention.restype = C.c_int
         L.idlm_isd_attention_ev.argtypes = L.idlm_isd_attention.argtypes + [vp]
         L.idlm_isd_attention_ev.restype = C.c_int
-        L.idlm_isd_attention_workspace.argtypes = [i32] * 8
+        L.idlm_isd_attention_workspace.argtypes = [i32] * 9
         L.idlm_isd_attention_workspace.restype = C.c_size_t
         L.idlm_isd_accept.argtypes = [vp, vp, C.c_uint64, vp, vp, i32, i32, i32, i32, vp, vp, C.c_uint32,
                                       vp, vp, C.c_size_t, vp]
@@ -120,8 +120,8 @@ def _dtype_code(t: torch.Tensor) -> int:
     raise TypeError("q/k/v must be bfloat16 or float32, got %s" % t.dtype)
 
 
-def idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype) -> int:
-    return int(lib().idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype))
+def idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, num_workgroups=0) -> int:
+    return int(lib().idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, num_workgroups))
 
 
 def _events_arg(events):
@@ -150,13 +150,13 @@ def idlm_isd_attention(q, k_cache, v_cache, block_table, ctx_lens, S, out, *, sc
     assert k_cache.stride(3) == 1 and k_cache.dtype == q.dtype and v_cache.dtype == q.dtype
     assert block_table.dtype == torch.int32 and ctx_lens.dtype == torch.int32
     assert block_table.is_contiguous() and ctx_lens.is_contiguous() and block_table.shape[0] == B
-    rc = lib().idlm_isd_attention_ev(
-        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
-        B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
-        k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale),
-        2 if k_operand_order else _dtype_code(q),
-        int(num_workgroups), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
-        _stream(stream), _events_arg(events))
+    args = (_ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_lens), S, _ptr(out),
+            B, Hq, Hkv, D, P, num_pages, block_table.shape[1],
+            k_cache.stride(0), k_cache.stride(1), k_cache.stride(2), float(scale),
+            2 if k_operand_order else _dtype_code(q),
+            int(num_workgroups), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+            _stream(stream))
+    rc = lib().idlm_isd_attention(*args) if events is None else lib().idlm_isd_attention_ev(*args, _events_arg(events))
     if rc != 0:
         raise IdlmError(rc, "idlm_isd_attention")
     return out
@@ -173,16 +173,23 @@ def idlm_isd_accept(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n
     n_draft: int (uniform) or int32 device tensor [B]; greedy: uint8 device tensor [B] or None.
     accept_len int32 [B] and new_tokens int32 [B,S] are written; draft_probs fp32 [B,S-1] optional.
     """
-    return _accept(lib().idlm_isd_accept_ev, "idlm_isd_accept", torch.float32, logits, draft_tokens, rng_seed,
+    return _accept(_with_or_without_events(lib().idlm_isd_accept, lib().idlm_isd_accept_ev), "idlm_isd_accept", torch.float32, logits, draft_tokens, rng_seed,
                    accept_len, new_tokens, n_draft, greedy, rng_offset, draft_probs, workspace, stream, events)
 
 
 def idlm_isd_accept_bf16(logits, draft_tokens, rng_seed, accept_len, new_tokens, *, n_draft, greedy=None,
                          rng_offset=0, draft_probs=None, workspace=None, stream=None, events=None):
     """The same acceptance over bf16 logits [B,S,V] (half the bytes per row; see idlm.h)."""
-    return _accept(lib().idlm_isd_accept_bf16_ev, "idlm_isd_accept_bf16", torch.bfloat16, logits, draft_tokens,
+    return _accept(_with_or_without_events(lib().idlm_isd_accept_bf16, lib().idlm_isd_accept_bf16_ev), "idlm_isd_accept_bf16", torch.bfloat16, logits, draft_tokens,
                    rng_seed, accept_len, new_tokens, n_draft, greedy, rng_offset, draft_probs, workspace, stream,
                    events)
+
+
+def _with_or_without_events(plain, hooked):
+    """The entry point of idlm.h unless timing events are given (then its *_ev form of idlm_debug.h)."""
+    def fn(*a):
+        return plain(*a[:16]) if a[16] is None else hooked(*a)
+    return fn
 
 
 def idlm_isd_accept_static_max_bytes() -> int:
@@ -375,7 +382,7 @@ def idlm_isd_accept_filtered_q(logits, draft_tokens, rng_seed, accept_len, new_t
 
 
 def idlm_isd_rng_dump(rng_seed, rng_offset, stream_tag, row0, n_rows, V, *, uniforms=None, gumbels=None, stream=None):
-    """The uniforms / Gumbel noise the acceptance pass draws for rows row0 .. row0+n_rows-1 (see idlm.h)."""
+    """The uniforms / Gumbel noise the acceptance pass draws for rows row0 .. row0+n_rows-1 (see idlm_debug.h)."""
     for a in (uniforms, gumbels):
         if a is not None:
             assert a.dtype == torch.float32 and tuple(a.shape) == (n_rows, V) and a.is_contiguous()

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <float.h>
 #include "../../include/idlm.h"
+#include "../../include/idlm_debug.h"
 
 #define IDLM_WAVE 64
 

@@ -37,7 +37,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
-constexpr int kMaxWorkgroups = 1024;   // upper bound of the persistent grid (sizes the workspace)
+constexpr int kMaxWorkgroups = 1024;      // upper bound of a forced persistent grid
+constexpr int kDefaultWorkgroups = 256;   // upper bound of the grid the library chooses itself (one workgroup per compute unit)
 
 struct AttnParams {
     const uint16_t* q;
@@ -782,17 +783,24 @@ static void row_tiling(int M, int* NB, int* RG)
 
 using namespace idlm;
 
+// bytes of the partial-result slots of a grid of W workgroups: two slots of 16*NB rows per wavefront
+static size_t partial_slots_bytes(int NB, int W)
+{
+    const size_t slots = (size_t)2 * W * 4;
+    return slots * NB * (4 * 64 * sizeof(u32x4) + 16 * sizeof(f32x4));
+}
+
 extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
-                                               int32_t P, int32_t max_pages_per_seq, int32_t dtype)
+                                               int32_t P, int32_t max_pages_per_seq, int32_t dtype,
+                                               int32_t num_workgroups)
 {
     int err;
     if (!shapes_ok(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, &err)) return 0;
+    if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return 0;
     if (!uses_mfma_path(D, dtype) || B == 0) return 0;
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
-    // two partial slots of 16*NB rows per wavefront of the largest grid
-    const size_t slots = (size_t)2 * kMaxWorkgroups * 4;
-    return slots * NB * (4 * 64 * sizeof(u32x4) + 16 * sizeof(f32x4));
+    return partial_slots_bytes(NB, num_workgroups ? num_workgroups : kDefaultWorkgroups);
 }
 
 extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
@@ -840,7 +848,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
         return launch_status();
     }
 
-    const size_t need = idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype);
+    const size_t need = idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, max_pages_per_seq, dtype, num_workgroups);
     if (!workspace || workspace_bytes < need) return IDLM_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return IDLM_ERR_ALIGN;
 
@@ -851,7 +859,7 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             return IDLM_ERR_LAUNCH;
-        W = cus > kMaxWorkgroups ? kMaxWorkgroups : cus;
+        W = cus > kDefaultWorkgroups ? kDefaultWorkgroups : cus;
         // A batch that cannot hold more than a few tiles per wavefront gets a smaller grid: slices
         // shorter than about 16 tiles only multiply the partial results that have to be joined.  The
         // bound uses what the host knows (B and the width of the block table).
@@ -862,6 +870,10 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
         if ((wavefronts + 3) / 4 < W) W = (int)((wavefronts + 3) / 4);
     }
 
+    // the slots of the grid that is launched fit: it is never larger than the one the workspace was sized for
+    int NB, RG_;
+    row_tiling(S * G, &NB, &RG_);
+
     AttnParams p;
     p.q = static_cast<const uint16_t*>(q);
     p.k = static_cast<const uint16_t*>(k_cache);
@@ -870,10 +882,9 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.M = S * G; p.max_pages = max_pages_per_seq;
     p.num_pages = num_pages;
     p.k_operand_order = dtype == IDLM_DTYPE_BF16_KOP;
-    int NB;
-    row_tiling(p.M, &NB, &p.RG);
+    p.RG = RG_;
     p.Mpad = 16 * NB;
-    const size_t slots = (size_t)2 * kMaxWorkgroups * 4;
+    const size_t slots = (size_t)2 * W * 4;
     p.ws_o = static_cast<u32x4*>(workspace);
     p.ws_ml = reinterpret_cast<f32x4*>(p.ws_o + slots * NB * 4 * 64);
     p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
@@ -883,12 +894,17 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     // per wavefront: Q operands of its current sequence, one parked partial result, that partial's row scalars
     const size_t shmem = (size_t)4 * NB * (4 * 64 * 16 * 2 + 16 * 16);
+    hipError_t attr = hipSuccess;
     if (NB == 4)   // beyond the default 64 KB limit
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<4>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     else if (NB == 2)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<2>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<2>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    if (attr != hipSuccess) {
+        (void)hipGetLastError();
+        return IDLM_ERR_LAUNCH;
+    }
     if (NB == 1) hipLaunchKernelGGL(isd_attention_bf16_kernel<1>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
     else if (NB == 2) hipLaunchKernelGGL(isd_attention_bf16_kernel<2>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
     else hipLaunchKernelGGL(isd_attention_bf16_kernel<4>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);

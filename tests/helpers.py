@@ -28,7 +28,7 @@ def gpu_attention(inp, num_workgroups=0, scale=0.0, k_operand_order=False):
     dcode = 1 if inp.q.dtype == torch.bfloat16 else 0
     B, S, Hq, D = inp.q.shape
     Hkv, P = inp.k_cache.shape[1], inp.k_cache.shape[2]
-    nbytes = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, inp.block_table.shape[1], dcode)
+    nbytes = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, inp.block_table.shape[1], dcode, num_workgroups)
     ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=inp.q.device)
     k_cache = inp.k_cache
     if k_operand_order:

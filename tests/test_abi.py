@@ -8,13 +8,16 @@ import pytest
 
 import paper_2604_11035_amd as idlm
 
-HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "idlm.h")
+INCLUDE = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+HEADERS = sorted(os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h"))
 
 
-def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(idlm_[a-z0-9_]+)\s*\(", text)))
+def declared_functions(headers=None):
+    names = set()
+    for h in headers or HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(idlm_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
@@ -24,6 +27,13 @@ def test_every_declared_symbol_is_exported():
     L = idlm.lib()
     for n in names:
         assert getattr(L, n) is not None, n
+    # the method's header holds the step's calls only; timing hooks, byte-counter calibration and the
+    # generator dump are declared apart
+    main = set(declared_functions([os.path.join(INCLUDE, "idlm.h")]))
+    aids = set(declared_functions([os.path.join(INCLUDE, "idlm_debug.h")])) - main
+    assert aids == {"idlm_isd_attention_ev", "idlm_isd_accept_ev", "idlm_isd_accept_bf16_ev", "idlm_isd_rng_dump",
+                    "idlm_stream_copy", "idlm_stream_read"}
+    assert not any(n.endswith("_ev") or n.startswith("idlm_stream") for n in main)
 
 
 def test_version_and_error_strings():
@@ -48,6 +58,12 @@ def test_workspace_sizes_are_host_only_and_monotone():
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 0) == 0   # fp32 path needs none
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64: the plain path needs none
     assert idlm.idlm_isd_attention_workspace(256, 33, 32, 8, 128, 16, 512, 1) == 0
+    # sized by the grid that will be launched: two slots of 64 rows (17 KB) per wavefront
+    assert w == 2 * 256 * 4 * 4 * (4 * 64 * 16 + 16 * 16)
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 1, 1024) == 4 * w
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 1, 64) == w // 4
+    assert idlm.idlm_isd_attention_workspace(256, 4, 32, 8, 128, 16, 512, 1) == w // 4      # 16 rows per KV head
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 1, 1025) == 0
 
 
 FAKE = C.c_void_p(0x1000)        # non-NULL, 16-byte aligned, never dereferenced (validation only)

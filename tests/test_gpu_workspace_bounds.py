@@ -64,9 +64,17 @@ def test_attention(name, kw):
     B, S, Hq, D = att.q.shape
     Hkv, P = att.k_cache.shape[1], att.k_cache.shape[2]
     out = torch.empty_like(att.q)
-    n = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, att.block_table.shape[1], 1)
-    _check(lambda ws: idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
-                                              workspace=ws), n, lambda: (out,))
+    for nwg in (0, 5, 300):
+        n = idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, att.block_table.shape[1], 1, nwg)
+        _check(lambda ws: idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
+                                                  num_workgroups=nwg, workspace=ws), n, lambda: (out,))
+    # a workspace sized for a smaller grid than the one asked for is refused
+    small = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, Hq, Hkv, D, P, att.block_table.shape[1], 1, 5)),
+                        dtype=torch.uint8, device=DEV)
+    with pytest.raises(idlm.IdlmError) as e:
+        idlm.idlm_isd_attention(att.q, att.k_cache, att.v_cache, att.block_table, att.ctx_lens, S, out,
+                                num_workgroups=300, workspace=small)
+    assert e.value.code == -5
 
 
 @pytest.mark.parametrize("B,S,d_in,d_out,r,tile,splits", [(23, 7, 320, 328, 64, 0, 0), (40, 9, 576, 264, 192, 128, 3),
