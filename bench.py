@@ -5,9 +5,14 @@ One "step" = one idlm_isd_attention call (one layer's paged stride attention) pl
 idlm_isd_accept call (introspective acceptance over the step's logits) on the large-
 concurrency serving workload (B=256, S=16; `serve256`), inputs resident in HBM.  Prints ONE
 JSON line: whole-step throughput in stride positions (tokens verified + proposed) per second,
-the roofline record of the dominant kernel (timed with HIP events recorded by the library
-around each of its kernels on every fourth timed step, on the stream they run on), and the CPU oracle timed on a bounded
-sample of the same workload on this machine's host cores.
+the roofline record of the dominant kernel (timed with HIP events that the library records
+around each of its kernels, on the stream they run on), the CPU oracle timed on the same
+workload on this machine's host cores, and a `configs` block with the per-kernel times of the
+other workloads (small, 8b, the long-context stride sweep).
+
+  python bench.py                                  the default line (everything)
+  python bench.py --sections step                  only the timed step and its kernels (profiling runs)
+  python bench.py --workload long32k --stride 16 --sections step
 """
 from __future__ import annotations
 
@@ -20,16 +25,12 @@ import time
 
 import numpy as np
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
-
-# HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
-# scaled by what the same counters read for idlm_stream_copy of known size); bytes per launch of
-# the named kernel on the named workload.  None where no measurement is committed under profiles/.
-MEASURED_TRAFFIC = {
-    ("serve256", "attention"): 3326077105,   # profiles/serve256_pmc_hbm_traffic.txt (1.025 x algorithmic)
-    ("serve256", "accept"): 2603501474,      # row-statistics kernel, same file (1.046 x algorithmic)
-}
+MIN_KERNEL_SAMPLES = 24         # launches timed with events per kernel
+CACHE_BYTES = 256 << 20         # memory-side cache: smaller working sets are rotated over several copies
+ROOT = os.path.dirname(os.path.abspath(__file__))
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
 
 
 class HipEvents:
@@ -39,7 +40,6 @@ class HipEvents:
         self.hip = C.CDLL("libamdhip64.so")
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
-        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
         self.hip.hipEventDestroy.argtypes = [C.c_void_p]
 
     def create(self, n):
@@ -64,18 +64,164 @@ class HipEvents:
             self.hip.hipEventDestroy(C.c_void_p(e))
 
 
+def measured_traffic(workload, kernel, lib_version):
+    """HBM bytes per launch of `kernel` on `workload` from the committed counter summary
+    (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size), or None when the
+    file has no line for this library version: a stale figure is never reported."""
+    try:
+        lines = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return None
+    for ln in lines:
+        f = ln.split()
+        if len(f) >= 4 and not ln.startswith("#") and f[0] == workload and f[1] == kernel:
+            kv = dict(x.split("=", 1) for x in f[2:] if "=" in x)
+            if int(kv.get("lib_version", -1)) == lib_version:
+                return int(kv["bytes"])
+    return None
+
+
 def attention_algorithmic_bytes(ctx_lens, cfg):
     """One read of every context token's K and V rows, Q in, O out, and the block table."""
-    kv = int(ctx_lens.sum()) * cfg.Hkv * cfg.D * 2 * 2
-    qo = cfg.B * 2 * cfg.S * cfg.Hq * cfg.D * 2
+    esz = 2 if cfg.dtype == "bf16" else 4
+    kv = int(ctx_lens.sum()) * cfg.Hkv * cfg.D * esz * 2
+    qo = cfg.B * 2 * cfg.S * cfg.Hq * cfg.D * esz
     table = int(((ctx_lens + cfg.P - 1) // cfg.P).sum()) * 4
     return kv + qo + table
 
 
 def attention_flops(ctx_lens, cfg):
     """2 contractions x 2 flop x D per (query row, head, visible key)."""
-    vis = sum(int(c) - cfg.S + i + 1 for c in ctx_lens for i in range(cfg.S))
+    c = ctx_lens.astype(np.int64)
+    vis = int((cfg.S * (c - cfg.S) + cfg.S * (cfg.S + 1) // 2).sum())
     return 4 * cfg.D * cfg.Hq * vis
+
+
+class Case:
+    """One workload resident in HBM, in `copies` identical copies at different addresses (launches
+    rotate over them so that a working set smaller than the memory-side cache is read cold)."""
+
+    def __init__(self, cfg, dev, copies=1, kop=True, workgroups=0):
+        import torch
+        import paper_2604_11035_amd as idlm
+        from isd_inputs import k_pages_in_operand_order, make_accept_inputs, make_attention_inputs
+        self.cfg, self.idlm, self.torch = cfg, idlm, torch
+        self.workgroups = workgroups
+        att = make_attention_inputs(cfg, device=dev)
+        acc = make_accept_inputs(cfg, device=dev)
+        self.att, self.acc = att, acc
+        B, S, V = cfg.B, cfg.S, cfg.V
+        self.kop = bool(kop) and cfg.dtype == "bf16" and cfg.D == 128
+        k_gpu = k_pages_in_operand_order(att.k_cache) if self.kop else att.k_cache
+        drafts = acc.draft_tokens[:, :S - 1].contiguous() if S > 1 else None
+        dcode = 1 if cfg.dtype == "bf16" else 0
+        max_pages = att.block_table.shape[1]
+        self.ws_att = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages,
+                                                                             dcode, workgroups)),
+                                  dtype=torch.uint8, device=dev)
+        self.ws_acc = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=dev)
+        self.accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+        self.new_tokens = torch.empty(B, S, dtype=torch.int32, device=dev)
+        self.draft_probs = torch.empty(B, max(S - 1, 1), dtype=torch.float32, device=dev)
+        self.drafts = drafts
+        self.k_gpu = k_gpu
+        self.out = torch.empty_like(att.q)
+        self.sets = [(att.q, k_gpu, att.v_cache, acc.logits, self.out)]
+        for _ in range(copies - 1):
+            self.sets.append((att.q.clone(), k_gpu.clone(), att.v_cache.clone(), acc.logits.clone(), torch.empty_like(att.q)))
+        self.ctx_np = att.ctx_lens.cpu().numpy().astype(np.int64)
+
+    def working_set_bytes(self):
+        q, k, v, lg, out = self.sets[0]
+        return sum(t.numel() * t.element_size() for t in (q, k, v, lg, out))
+
+    def step(self, i, stream, ev_att=None, ev_acc=None):
+        cfg, att, acc, idlm = self.cfg, self.att, self.acc, self.idlm
+        q, k, v, lg, out = self.sets[i % len(self.sets)]
+        idlm.idlm_isd_attention(q, k, v, att.block_table, att.ctx_lens, cfg.S, out, num_workgroups=self.workgroups,
+                                workspace=self.ws_att, stream=stream, events=ev_att, k_operand_order=self.kop)
+        idlm.idlm_isd_accept(lg, self.drafts, acc.rng_seed, self.accept_len, self.new_tokens, n_draft=acc.n_draft,
+                             greedy=acc.greedy, rng_offset=i, draft_probs=self.draft_probs if cfg.S > 1 else None,
+                             workspace=self.ws_acc, stream=stream, events=ev_acc)
+
+
+def copies_for(cfg_bytes):
+    """Copies needed so that consecutive launches never find their inputs in the memory-side cache."""
+    if cfg_bytes >= 4 * CACHE_BYTES:
+        return 1
+    return int(min(16, max(2, -(-3 * CACHE_BYTES // max(cfg_bytes, 1)))))
+
+
+def stats_of(samples):
+    v = sorted(samples)
+    return {"ms": sum(v) / len(v), "min_ms": v[0], "median_ms": v[len(v) // 2], "max_ms": v[-1], "samples": len(v)}
+
+
+def kernel_record(case, hev, events):
+    """Per-kernel figures from the hooked launches: events = [(attention events, accept events), ...]."""
+    cfg = case.cfg
+    t = {name: stats_of([hev.elapsed_ms(e[w][a], e[w][b]) for e in events])
+         for name, (w, a, b) in {"attention": (0, 0, 1), "merge": (0, 1, 2), "row_stats": (1, 0, 1), "tail": (1, 1, 2)}.items()}
+    att_bytes = attention_algorithmic_bytes(case.ctx_np, cfg)
+    att_flops = attention_flops(case.ctx_np, cfg)
+    acc_bytes = cfg.B * cfg.S * cfg.V * 4
+    a, r = t["attention"], t["row_stats"]
+    mfma = cfg.dtype == "bf16" and cfg.D == 128
+    kernels = {
+        ("isd_attention_bf16_kernel" if mfma else "isd_attention_f32_kernel"): dict(
+            a, algorithmic_bytes=att_bytes, GBps=att_bytes / a["ms"] / 1e6, frac_hbm=att_bytes / a["ms"] / 1e6 / HBM_PEAK_GBS,
+            TFLOPs=att_flops / a["ms"] / 1e9, frac_mfma=att_flops / a["ms"] / 1e9 / MFMA_BF16_PEAK_TFLOPS),
+        "isd_attention_merge_kernel": {"ms": t["merge"]["ms"]},
+        "isd_row_stats_kernel": dict(r, algorithmic_bytes=acc_bytes, GBps=acc_bytes / r["ms"] / 1e6,
+                                     frac_hbm=acc_bytes / r["ms"] / 1e6 / HBM_PEAK_GBS),
+        "isd_accept_chain+sample+emit_kernels": {"ms": t["tail"]["ms"]},
+    }
+    return kernels
+
+
+def hooked_launches(case, hev, stream, n, first_index):
+    torch = case.torch
+    events = [(hev.create(3), hev.create(3)) for _ in range(n)]
+    for j, (ea, eb) in enumerate(events):
+        case.step(first_index + j, stream, ea, eb)
+    torch.cuda.synchronize()
+    return events
+
+
+def config_line(name, cfg, dev, hev, stream):
+    """Compact per-kernel record of one of the other workloads: >= MIN_KERNEL_SAMPLES hooked launches,
+    inputs rotated over enough copies that a small working set is read from HBM, not from the cache."""
+    import torch
+    probe = Case(cfg, dev, copies=1)
+    nbytes = probe.working_set_bytes()
+    n = copies_for(nbytes)
+    case = probe
+    if n > 1:
+        del probe
+        case = Case(cfg, dev, copies=n)
+    for i in range(3):
+        case.step(i, stream)
+    torch.cuda.synchronize()
+    ev = hooked_launches(case, hev, stream, MIN_KERNEL_SAMPLES, 3)
+    k = kernel_record(case, hev, ev)
+    for ea, eb in ev:
+        hev.destroy(ea + eb)
+    att = next(v for kk, v in k.items() if kk.startswith("isd_attention_") and "merge" not in kk)
+    rs = k["isd_row_stats_kernel"]
+    rec = {
+        "shape": "B=%d S=%d Hq=%d Hkv=%d D=%d V=%d ctx %s [%d,%d]" % (cfg.B, cfg.S, cfg.Hq, cfg.Hkv, cfg.D, cfg.V, cfg.ctx_kind,
+                                                                    cfg.ctx_lo or min(cfg.ctx_list or (0,)),
+                                                                    cfg.ctx_hi or max(cfg.ctx_list or (0,))),
+        "input_copies_rotated": n, "working_set_MB": round(nbytes / 1e6, 1), "samples": att["samples"],
+        "attention_ms": att["ms"], "attention_median_ms": att["median_ms"], "attention_frac_hbm": att["frac_hbm"],
+        "attention_frac_mfma": att["frac_mfma"], "attention_merge_ms": k["isd_attention_merge_kernel"]["ms"],
+        "row_stats_ms": rs["ms"], "row_stats_median_ms": rs["median_ms"], "row_stats_frac_hbm": rs["frac_hbm"],
+        "accept_tail_ms": k["isd_accept_chain+sample+emit_kernels"]["ms"],
+        "rows_per_kv_head": cfg.S * cfg.G,
+    }
+    del case
+    torch.cuda.empty_cache()
+    return rec
 
 
 def cpu_baseline(att, acc, cfg, n_seq, threads=0):
@@ -119,150 +265,14 @@ def cpu_baseline(att, acc, cfg, n_seq, threads=0):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="serve256")
-    ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
-    ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
-    ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
-    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle (0 = all the box gives it)")
-    ap.add_argument("--k-operand-order", type=int, default=1,
-                    help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
-                 % args.gpus)
-
+def extras(case, args, hev, stream, dev, ms_per_step):
+    """Everything around the step that is reported but not part of `value`."""
     import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
-    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
-    import paper_2604_11035_amd as idlm
-    from isd_inputs import get_config, make_accept_inputs, make_attention_inputs
-
-    cfg = get_config(args.workload, **({"S": args.stride} if args.stride else {}))
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    att = make_attention_inputs(cfg, device=dev)
-    acc = make_accept_inputs(cfg, device=dev)
+    idlm, cfg, att, acc = case.idlm, case.cfg, case.att, case.acc
     B, S, V = cfg.B, cfg.S, cfg.V
-    dcode = 1 if cfg.dtype == "bf16" else 0
-    max_pages = att.block_table.shape[1]
-    nwg = args.workgroups or torch.cuda.get_device_properties(0).multi_processor_count
-    ws_att = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, max_pages,
-                                                                    dcode)),
-                         dtype=torch.uint8, device=dev)
-    ws_acc = torch.empty(max(256, idlm.idlm_isd_accept_workspace(B, S, V)), dtype=torch.uint8, device=dev)
-    out = torch.empty_like(att.q)
-    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
-    new_tokens = torch.empty(B, S, dtype=torch.int32, device=dev)
-    draft_probs = torch.empty(B, max(S - 1, 1), dtype=torch.float32, device=dev)
-    drafts = acc.draft_tokens[:, :S - 1].contiguous() if S > 1 else None
-
-    hev = HipEvents()
-    stream = torch.cuda.current_stream()
-    kop = bool(args.k_operand_order) and cfg.dtype == "bf16"
-    k_gpu = att.k_cache
-    if kop:   # the same pool, pages permuted once (what idlm_isd_kv_append maintains when given the same option)
-        from isd_inputs import k_pages_in_operand_order
-        k_gpu = k_pages_in_operand_order(att.k_cache)
-
-    def step(i, ev_att=None, ev_acc=None):
-        idlm.idlm_isd_attention(att.q, k_gpu, att.v_cache, att.block_table, att.ctx_lens, S, out,
-                                num_workgroups=args.workgroups, workspace=ws_att, stream=stream, events=ev_att,
-                                k_operand_order=kop)
-        idlm.idlm_isd_accept(acc.logits, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft,
-                             greedy=acc.greedy, rng_offset=i, draft_probs=draft_probs if S > 1 else None,
-                             workspace=ws_acc, stream=stream, events=ev_acc)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    # every fourth timed step carries the library's event hooks (each recorded event separates two
-    # kernels by a few microseconds, so hooking every step would slow the step it measures by 3-4 %)
-    hooked = [i for i in range(args.steps) if i % 4 == 0]
-    events = [(hev.create(3), hev.create(3)) for _ in hooked]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i % 4 == 0:
-            step(args.warmup + i, events[i // 4][0], events[i // 4][1])
-        else:
-            step(args.warmup + i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    # what the last timed step accepted on these synthetic inputs (bookkeeping on the outputs): the
-    # introspective acceptance rate is the mean accept probability of the verified drafts, here p(draft)
-    acceptance = None
-    if S > 1:
-        nd_f = acc.n_draft.clamp(max=S - 1).float()
-        verified = torch.arange(S - 1, device=dev)[None, :] < acc.n_draft[:, None]
-        stochastic = (acc.greedy == 0) if acc.greedy is not None else torch.ones(B, dtype=torch.bool, device=dev)
-        acceptance = {
-            "mean_drafts_per_sequence": float(nd_f.mean().item()),
-            "mean_accept_len": float(accept_len.float().mean().item()),
-            "tokens_finalised_per_sequence_per_step": float((accept_len.float() + 1).mean().item()),
-            "introspective_acceptance_rate_mean_p_draft": float(draft_probs[verified].mean().item()) if bool(verified.any()) else None,
-            "stochastic_share": float(stochastic.float().mean().item()),
-        }
-
-    def avg(which, a, b):
-        return sum(hev.elapsed_ms(e[which][a], e[which][b]) for e in events) / len(events)
-
-    def spread(which, a, b):
-        v = sorted(hev.elapsed_ms(e[which][a], e[which][b]) for e in events)
-        return {"min_ms": v[0], "median_ms": v[len(v) // 2], "max_ms": v[-1], "samples": len(v)}
-
-    t_att_main, t_att_merge = avg(0, 0, 1), avg(0, 1, 2)
-    t_acc_stats, t_acc_final = avg(1, 0, 1), avg(1, 1, 2)
-    spreads = {"isd_attention_bf16_kernel": spread(0, 0, 1), "isd_row_stats_kernel": spread(1, 0, 1)}
-    for ea, eb in events:
-        hev.destroy(ea + eb)
-
-    ctx_np = att.ctx_lens.cpu().numpy().astype(np.int64)
-    att_bytes = attention_algorithmic_bytes(ctx_np, cfg)
-    acc_bytes = B * S * V * 4
-    att_flops = attention_flops(ctx_np, cfg)
-    kernels = {
-        "isd_attention_bf16_kernel": {
-            "ms": t_att_main, "algorithmic_bytes": att_bytes, "GBps": att_bytes / t_att_main / 1e6,
-            "frac_hbm": att_bytes / t_att_main / 1e6 / HBM_PEAK_GBS,
-            "TFLOPs": att_flops / t_att_main / 1e9, "frac_mfma": att_flops / t_att_main / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-            "workgroups": nwg},
-        "isd_attention_merge_kernel": {"ms": t_att_merge},
-        "isd_row_stats_kernel": {
-            "ms": t_acc_stats, "algorithmic_bytes": acc_bytes, "GBps": acc_bytes / t_acc_stats / 1e6,
-            "frac_hbm": acc_bytes / t_acc_stats / 1e6 / HBM_PEAK_GBS},
-        "isd_accept_chain+sample+emit_kernels": {"ms": t_acc_final},
-    }
-    for name, sp in spreads.items():
-        kernels[name].update(sp)
-    t_att_call, t_acc_call = t_att_main + t_att_merge, t_acc_stats + t_acc_final
-    per_call = {
-        "attention_positions_per_s": B * S / (t_att_call / 1e3), "accept_positions_per_s": B * S / (t_acc_call / 1e3),
-        # context only: a forward of the 8B-class model the paper converts has 36 attention layers per acceptance
-        # pass; its linear layers are not part of this figure
-        "model_shaped_positions_per_s_36_attention_layers_no_gemms": B * S / ((36 * t_att_call + t_acc_call) / 1e3),
-    }
-    if t_att_main >= t_acc_stats:
-        dom, dom_name, dom_key = kernels["isd_attention_bf16_kernel"], "isd_attention_bf16_kernel", "attention"
-    else:
-        dom, dom_name, dom_key = kernels["isd_row_stats_kernel"], "isd_row_stats_kernel", "accept"
-    roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": dom["GBps"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((args.workload, dom_key)),
-                "kernel": dom_name, "ms": dom["ms"]}
-
-    # plain streaming kernels of known size: practical bandwidth ceiling of this device, and the
-    # reference that hardware byte counters are scaled by in the committed profiles (4 GiB, so that
-    # the 256 MB memory-side cache holds a negligible part of it from one pass to the next)
-    probe = torch.empty(1 << 32, dtype=torch.uint8, device=dev)
-    probe_dst = torch.empty_like(probe)
-    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    kop, k_gpu, drafts, out = case.kop, case.k_gpu, case.drafts, case.out
+    accept_len, new_tokens = case.accept_len, case.new_tokens
+    res = {}
 
     def timed(fn, n=5):
         fn()
@@ -275,45 +285,42 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b_) / n
 
+    # plain streaming kernels of known size: practical bandwidth ceiling of this device, and the
+    # reference that hardware byte counters are scaled by in the committed profiles (4 GiB, so that
+    # the 256 MB memory-side cache holds a negligible part of it from one pass to the next)
+    probe = torch.empty(1 << 32, dtype=torch.uint8, device=dev)
+    probe_dst = torch.empty_like(probe)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
     t_read = timed(lambda: idlm.idlm_stream_read(probe, sink))
     t_copy = timed(lambda: idlm.idlm_stream_copy(probe, probe_dst))
-    stream_probe = {"read_GBps": probe.numel() / t_read / 1e6, "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6,
-              "bytes": probe.numel()}
-    for name in ("isd_attention_bf16_kernel", "isd_row_stats_kernel"):
-        kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / stream_probe["read_GBps"]
+    res["stream_ceiling"] = {"read_GBps": probe.numel() / t_read / 1e6,
+                             "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6, "bytes": probe.numel()}
     del probe, probe_dst
 
     # the same step launched without the timing hooks, and replayed from a captured HIP graph (the
     # calls allocate nothing and never synchronise, so they can be captured as they are)
-    def plain_steps(n):
-        for i in range(n):
-            step(args.warmup + i)
+    cur = torch.cuda.current_stream()
     torch.cuda.synchronize()
-    t_plain = timed(lambda: plain_steps(args.steps), n=1) / args.steps
+    t_plain = timed(lambda: [case.step(args.warmup + i, cur) for i in range(args.steps)], n=1) / args.steps
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
-    stream = side
     with torch.cuda.graph(graph, stream=side):
-        step(0)
-    stream = torch.cuda.current_stream()
+        case.step(0, side)
     torch.cuda.synchronize()
+    t_graph = timed(lambda: [graph.replay() for _ in range(args.steps)], n=1) / args.steps
+    res["launch_modes"] = {"timed_region_ms": ms_per_step, "eager_ms": t_plain, "graph_replay_ms": t_graph}
 
-    def replay_steps(n):
-        for _ in range(n):
-            graph.replay()
-    t_graph = timed(lambda: replay_steps(args.steps), n=1) / args.steps
     # the attention call alone with the K pool in the other page layout (slot-major rows / operand order)
-    k_other = att.k_cache
-    if not kop and cfg.dtype == "bf16":
+    if cfg.dtype == "bf16" and cfg.D == 128:
         from isd_inputs import k_pages_in_operand_order
-        k_other = k_pages_in_operand_order(att.k_cache)
-    t_att_kop, t_att_other = (timed(lambda: idlm.idlm_isd_attention(
-        att.q, kk, att.v_cache, att.block_table, att.ctx_lens, S, out, num_workgroups=args.workgroups, workspace=ws_att,
-        k_operand_order=flag), n=10) for kk, flag in ((k_gpu, kop), (k_other, (not kop) and cfg.dtype == "bf16")))
-    del k_other
-    launch_modes = {"timed_region_ms": ms_per_step, "eager_ms": t_plain, "graph_replay_ms": t_graph}
-    k_layouts = {"attention_call_ms_as_timed": t_att_kop, "attention_call_ms_other_k_page_layout": t_att_other,
-                 "timed_layout": "operand order" if kop else "slot-major"}
+        k_other = att.k_cache if kop else k_pages_in_operand_order(att.k_cache)
+        t_a, t_b = (timed(lambda: idlm.idlm_isd_attention(att.q, kk, att.v_cache, att.block_table, att.ctx_lens, S, out,
+                                                          num_workgroups=args.workgroups, workspace=case.ws_att,
+                                                          k_operand_order=flag), n=10)
+                    for kk, flag in ((k_gpu, kop), (k_other, not kop)))
+        del k_other
+        res["k_page_layouts"] = {"attention_call_ms_as_timed": t_a, "attention_call_ms_other_k_page_layout": t_b,
+                                 "timed_layout": "operand order" if kop else "slot-major"}
 
     # the two small kernels between steps (scatter of the stride's K/V rows; trim-and-commit and next
     # stride), timed on the same workload outside the timed region above
@@ -341,7 +348,7 @@ def main():
                                                   mask_token=cfg.V - 1, P=cfg.P), n=20)
     commit_ok = all(int(st_["status"].item()) == 0 for st_ in states)
     append_bytes = 2 * 2 * B * S * cfg.Hkv * cfg.D * att.q.element_size()
-    loop_kernels = {
+    res["between_steps"] = {
         "isd_kv_append_kernel": {"ms": t_append, "bytes_read_plus_written": append_bytes,
                                  "GBps": append_bytes / t_append / 1e6},
         "isd_commit_kernel": {"ms": t_commit, "status_ok": commit_ok},
@@ -394,6 +401,7 @@ def main():
                 sample_proposals=True, q_cand=rec[0], q_row=q_row1, cand_out=rec[1]), n=5)
             del lg16f
         del rec
+    res["accept_general"] = gen
 
     # the acceptance pass over the same logits stored as bf16 (half the bytes per row); not the timed path,
     # whose logits are fp32 as the metric's workload states
@@ -404,7 +412,7 @@ def main():
         t_stats = []
         for i in range(6):
             idlm.idlm_isd_accept_bf16(lg16, drafts, acc.rng_seed, accept_len, new_tokens, n_draft=acc.n_draft,
-                                      greedy=acc.greedy, workspace=ws_acc, stream=stream, events=evs)
+                                      greedy=acc.greedy, workspace=case.ws_acc, stream=stream, events=evs)
             torch.cuda.synchronize()
             if i:
                 t_stats.append((hev.elapsed_ms(evs[0], evs[1]), hev.elapsed_ms(evs[1], evs[2])))
@@ -415,6 +423,7 @@ def main():
                     "algorithmic_bytes": rs_bytes, "GBps": rs_bytes / t_rs / 1e6,
                     "frac_hbm": rs_bytes / t_rs / 1e6 / 8000.0}
         del lg16
+    res["accept_bf16_logits"] = bf16_acc
 
     # one linear layer of the lossless variant (gated low-rank adapter) on this step's tokens: an attention
     # projection of the 8B-class model (d_in = d_out = Hq*D) with the paper's rank-128 adapter, MASK rows from
@@ -441,10 +450,115 @@ def main():
                     "frac_mfma": flops / t_full / 1e9 / 2500.0}
         lora = {"step_tokens": lora_case(B, S, acc.n_draft.clamp(max=S - 1)),
                 "paper_serving_shape_64x7": lora_case(64, 7, torch.full((64,), 3, dtype=torch.int32, device=dev))}
+    res["gated_lora_linear"] = lora
+    return res
 
-    cpu = None
-    if args.cpu_sample > 0:
-        cpu = cpu_baseline(att, acc, cfg, min(args.cpu_sample, B), args.cpu_threads)
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="serve256")
+    ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
+    ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle (0 = all the box gives it)")
+    ap.add_argument("--k-operand-order", type=int, default=1,
+                    help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
+    ap.add_argument("--sections", default="all",
+                    help="comma list of step,cpu,extras,configs (all = every one; configs only with the default workload)")
+    ap.add_argument("--copies", type=int, default=0, help="input copies the launches rotate over (0 = as many as the "
+                                                          "memory-side cache needs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
+                 % args.gpus)
+    sections = {"step", "cpu", "extras", "configs"} if args.sections == "all" else set(args.sections.split(","))
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    sys.path.insert(0, ROOT)
+    import paper_2604_11035_amd as idlm
+    from isd_inputs import get_config
+    from isd_inputs.configs import LONG32K_STRIDES
+
+    cfg = get_config(args.workload, **({"S": args.stride} if args.stride else {}))
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    hev = HipEvents()
+    stream = torch.cuda.current_stream()
+    probe = Case(cfg, dev, copies=1, kop=args.k_operand_order, workgroups=args.workgroups)
+    ncopies = args.copies or copies_for(probe.working_set_bytes())
+    case = probe if ncopies == 1 else Case(cfg, dev, copies=ncopies, kop=args.k_operand_order, workgroups=args.workgroups)
+    del probe
+    B, S, V = cfg.B, cfg.S, cfg.V
+    nwg = args.workgroups or torch.cuda.get_device_properties(0).multi_processor_count
+
+    for i in range(args.warmup):
+        case.step(i, stream)
+    torch.cuda.synchronize()
+    # Every second timed step carries the library's event hooks (each recorded event separates two kernels by a
+    # few microseconds, so a hooked step is 3-4 % slower than a plain one); more hooked launches follow the
+    # timed region until every kernel has MIN_KERNEL_SAMPLES samples.
+    hooked = [i for i in range(args.steps) if i % 2 == 0]
+    events = [(hev.create(3), hev.create(3)) for _ in hooked]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if i % 2 == 0:
+            case.step(args.warmup + i, stream, events[i // 2][0], events[i // 2][1])
+        else:
+            case.step(args.warmup + i, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    in_region = len(events)
+    if in_region < MIN_KERNEL_SAMPLES:
+        events += hooked_launches(case, hev, stream, MIN_KERNEL_SAMPLES - in_region, args.warmup + args.steps)
+    kernels = kernel_record(case, hev, events)
+    for ea, eb in events:
+        hev.destroy(ea + eb)
+
+    # what the last step accepted on these synthetic inputs (bookkeeping on the outputs): the introspective
+    # acceptance rate is the mean accept probability of the verified drafts, here p(draft)
+    acc = case.acc
+    acceptance = None
+    if S > 1:
+        nd_f = acc.n_draft.clamp(max=S - 1).float()
+        verified = torch.arange(S - 1, device=dev)[None, :] < acc.n_draft[:, None]
+        stochastic = (acc.greedy == 0) if acc.greedy is not None else torch.ones(B, dtype=torch.bool, device=dev)
+        acceptance = {
+            "mean_drafts_per_sequence": float(nd_f.mean().item()),
+            "mean_accept_len": float(case.accept_len.float().mean().item()),
+            "tokens_finalised_per_sequence_per_step": float((case.accept_len.float() + 1).mean().item()),
+            "introspective_acceptance_rate_mean_p_draft": float(case.draft_probs[verified].mean().item()) if bool(verified.any()) else None,
+            "stochastic_share": float(stochastic.float().mean().item()),
+        }
+
+    att_name = next(k for k in kernels if k.startswith("isd_attention_") and "merge" not in k)
+    kernels[att_name]["workgroups"] = nwg
+    for k in (att_name, "isd_row_stats_kernel"):
+        kernels[k]["samples_in_timed_region"] = in_region
+    t_att_call = kernels[att_name]["ms"] + kernels["isd_attention_merge_kernel"]["ms"]
+    t_acc_call = kernels["isd_row_stats_kernel"]["ms"] + kernels["isd_accept_chain+sample+emit_kernels"]["ms"]
+    per_call = {
+        "attention_positions_per_s": B * S / (t_att_call / 1e3), "accept_positions_per_s": B * S / (t_acc_call / 1e3),
+        # context only: a forward of the 8B-class model the paper converts has 36 attention layers per acceptance
+        # pass; its linear layers are not part of this figure
+        "model_shaped_positions_per_s_36_attention_layers_no_gemms": B * S / ((36 * t_att_call + t_acc_call) / 1e3),
+    }
+    if kernels[att_name]["ms"] >= kernels["isd_row_stats_kernel"]["ms"]:
+        dom_name, dom_key = att_name, "attention"
+    else:
+        dom_name, dom_key = "isd_row_stats_kernel", "row_stats"
+    dom = kernels[dom_name]
+    version = idlm.idlm_version()
+    roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dom["GBps"] / HBM_PEAK_GBS,
+                "traffic": measured_traffic(cfg.name + ("" if not args.stride else "_S%d" % args.stride), dom_key, version),
+                "kernel": dom_name, "ms": dom["ms"], "samples": dom["samples"], "lib_version": version}
 
     line = {
         "metric": "ISD tokens verified+proposed/sec at B=256 on 1 GPU; % of peak HBM GB/s",
@@ -462,24 +576,31 @@ def main():
         "config": {"workload": "%s: B=%d S=%d Hq=%d Hkv=%d D=%d P=%d V=%d, ctx %s [%d,%d] (sum %d), one attention "
                                "layer + one acceptance pass per step"
                                % (cfg.name, B, S, cfg.Hq, cfg.Hkv, cfg.D, cfg.P, V, cfg.ctx_kind, cfg.ctx_lo,
-                                  cfg.ctx_hi, int(ctx_np.sum())),
-                   "attention_workgroups": nwg, "logits_dtype": "f32",
-                   "k_pages": "operand order" if kop else "slot-major"},
+                                  cfg.ctx_hi, int(case.ctx_np.sum())),
+                   "attention_workgroups": nwg, "logits_dtype": "f32", "input_copies_rotated": ncopies,
+                   "k_pages": "operand order" if case.kop else "slot-major"},
         "roofline": roofline,
-        "cpu_baseline": cpu,
+        "cpu_baseline": None,
         "kernels": kernels,
         "per_call": per_call,
-        "stream_ceiling": stream_probe,
-        "between_steps": loop_kernels,
-        "launch_modes": launch_modes,
-        "k_page_layouts": k_layouts,
         "acceptance": acceptance,
-        "accept_general": gen,
-        "accept_bf16_logits": bf16_acc,
-        "gated_lora_linear": lora,
-        "hbm_frac_both": {"attention": kernels["isd_attention_bf16_kernel"]["frac_hbm"],
-                          "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
+        "hbm_frac_both": {"attention": kernels[att_name]["frac_hbm"], "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }
+    if "extras" in sections:
+        line.update(extras(case, args, hev, stream, dev, ms_per_step))
+        for name in (att_name, "isd_row_stats_kernel"):
+            kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / line["stream_ceiling"]["read_GBps"]
+    if "cpu" in sections and args.cpu_sample > 0:
+        line["cpu_baseline"] = cpu_baseline(case.att, case.acc, cfg, min(args.cpu_sample, B), args.cpu_threads)
+    if "configs" in sections and args.workload == "serve256" and not args.stride:
+        del case
+        torch.cuda.empty_cache()
+        configs = {}
+        for name, strides in (("small", (0,)), ("8b", (0,)), ("long32k", LONG32K_STRIDES)):
+            for s_ in strides:
+                c = get_config(name, **({"S": s_} if s_ else {}))
+                configs[name + ("_S%d" % s_ if s_ else "")] = config_line(name, c, dev, hev, stream)
+        line["configs"] = configs
     print(json.dumps(line))
 
 

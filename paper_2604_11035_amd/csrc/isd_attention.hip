@@ -355,10 +355,19 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             }
             int pb = b, pkt = kt, pnt = nt;   // cursor of the tile after this sequence's last one
 
-            for (int t = 0; t < n_in; ++t, ++i) {
-                const int tb = 32 * (kt + t);
-                // ---- St = K Qt (Q operands are read back from LDS four registers at a time) ----
-                f32x4 sacc[NB][2];
+            // One tile in three parts, so that the loop below holds nothing but the common case: the running
+            // reference exponent of a row is raised (and the row's accumulators rescaled) only when a score
+            // overshoots it by kRescaleSlack powers of two, which after a row's first tile practically never
+            // happens.  A first tile needs no rescale either (its accumulators are still zero), so the tile loop
+            // leaves through its side exit only for a later overshoot, the rescale is done out there, and the loop
+            // is entered again.  The accumulators are then loop-carried through matrix instructions alone and
+            // stay in accumulation registers; with the rescale inside the loop they were copied out to vector
+            // registers at the top of every tile.
+            f32x4 sacc[NB][2];
+            float lmax[NB];
+            auto scores = [&](int tb) {
+                asm volatile("" ::: "memory");   // Q comes out of LDS anew for every tile instead of staying in registers
+                // ---- St = K Qt ----
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     sacc[nb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -389,9 +398,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     for (int jj = 0; jj < 8; ++jj)
                         if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) tv[jj] = u32x4{0u, 0u, 0u, 0u};
                 }
-                // ---- running reference exponent: rescale only when a score overshoots it ----
                 bool overshoot = false;
-                float lmax[NB];
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), fmaxf(sacc[nb][0][2], sacc[nb][0][3]));
@@ -399,20 +406,18 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     lmax[nb] = mx * cs;
                     overshoot |= lmax[nb] > mref[nb] + kRescaleSlack;
                 }
-                if (__any(overshoot)) {
+                return __any(overshoot) != 0;
+            };
+            // the largest score of each row of the tile (the four lanes that share a row agree on it)
+            auto row_max = [&](float (&rm)[NB]) {
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        float rm = lmax[nb];
-                        rm = fmaxf(rm, __shfl_xor(rm, 16));
-                        rm = fmaxf(rm, __shfl_xor(rm, 32));
-                        const float mnew = fmaxf(mref[nb], rm);
-                        const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
-                        lsum[nb] *= alpha;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
-                        mref[nb] = mnew;
-                    }
+                for (int nb = 0; nb < NB; ++nb) {
+                    float x = lmax[nb];
+                    x = fmaxf(x, __shfl_xor(x, 16));
+                    rm[nb] = fmaxf(x, __shfl_xor(x, 32));
                 }
+            };
+            auto weights_and_values = [&]() {
                 // ---- Pt = 2^(St*scale - ref), packed straight into B-operand order ----
                 bf16x8 pt[NB];
 #pragma unroll
@@ -449,6 +454,42 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 if (i + 2 < remaining) {
                     advance(c1b, c1kt, c1nt);
                     page_ids(c1b, c1kt, npg0, npg1);
+                }
+            };
+
+            for (int t = 0; t < n_in;) {
+                bool rescale = false;
+                for (; t < n_in; ++t, ++i) {
+                    if (scores(32 * (kt + t))) {
+                        // rows that have not seen a key yet take the tile's maximum as their reference (their
+                        // accumulators are zero); any other overshoot leaves the loop
+                        float rm[NB];
+                        row_max(rm);
+                        bool late = false;
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const bool fresh = mref[nb] == -INFINITY;
+                            late |= !fresh && rm[nb] > mref[nb] + kRescaleSlack;
+                            mref[nb] = fresh ? rm[nb] : mref[nb];
+                        }
+                        if (__any(late)) { rescale = true; break; }
+                    }
+                    weights_and_values();
+                }
+                if (rescale) {
+                    float rm[NB];
+                    row_max(rm);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        const float mnew = fmaxf(mref[nb], rm[nb]);
+                        const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
+                        lsum[nb] *= alpha;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
+                        mref[nb] = mnew;
+                    }
+                    weights_and_values();
+                    ++t; ++i;
                 }
             }
 
