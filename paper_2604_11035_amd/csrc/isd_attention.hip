@@ -49,7 +49,6 @@ struct AttnParams {
                     //                   last): eight fp16 per entry, normalised per row to a largest magnitude of 1
     f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator l, largest magnitude of O / l, unused
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
-    int k_operand_order;   // K pages hold their 16-byte chunks in MFMA operand order (IDLM_DTYPE_BF16_KOP)
     int num_pages;
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
@@ -199,7 +198,11 @@ __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32
 // slice tile by tile, switching sequence (new Q, fresh accumulators, output written) whenever
 // the slice crosses into the next one, with the next tile's K/V always in flight - also across
 // such a switch.
-template <int NB>
+//
+// LAYOUT fixes the strides inside a page at compile time, so that the eight loads of an operand share
+// one address and differ in their immediate offsets: 0 = any strides (token-major pools, padded rows),
+// 1 = contiguous slot-major pages (token_stride = 128), 2 = the same with the K pages in operand order.
+template <int NB, int LAYOUT>
 __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParams p,
                                                                  const int32_t* __restrict__ block_table,
                                                                  const int32_t* __restrict__ ctx_lens)
@@ -270,29 +273,40 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         };
         bf16x8 tk[2][4];   // K of the current tile: [16-token block][k-step], A operand of St
         u32x4 tv[8];       // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
-        // Addresses are a wave-uniform 64-bit page base plus a 32-bit lane offset (the host checks that
-        // the offset fits): one address register per lane instead of a 64-bit pair per page.
+        // Addresses are a wave-uniform 64-bit page base (scalar registers) plus a 32-bit lane offset in bytes
+        // (the host checks that it fits) plus, for the fixed layouts, an immediate: one address per operand and
+        // page instead of one per load.
         // K pages in operand order: the 16 bytes that lane l needs for k-step s sit at entry 64*s + l of the
         // page's 4 KB block, so a load instruction reads 1 KB of whole cache lines instead of 16 rows x 64 bytes
-        const uint32_t klane = p.k_operand_order ? (uint32_t)(lane * 8) : (uint32_t)(n * (int)p.token_stride + g * 8);
-        const int kstep = p.k_operand_order ? 512 : 32;
-        const uint32_t vlane = (uint32_t)(4 * g * (int)p.token_stride + n * 8);
+        typedef const __attribute__((address_space(1))) char* gbytes;
+        typedef const __attribute__((address_space(1))) u32x4* gvec;
+        const int tstride = LAYOUT == 0 ? (int)p.token_stride : 128;
+        const uint32_t klane = LAYOUT == 2 ? (uint32_t)(lane * 16) : (uint32_t)(2 * (n * tstride + g * 8));
+        const int kstep = LAYOUT == 2 ? 1024 : 64;
+        const uint32_t vlane = (uint32_t)(2 * (4 * g * tstride + n * 8));
+        const int vstep = 2 * tstride;
+        auto page_base = [&](const uint16_t* pool, int pg) {
+            const uint64_t a = reinterpret_cast<uint64_t>(pool) + 2 * (uint64_t)pg * (uint64_t)p.page_stride;
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+            return (gbytes)(((uint64_t)hi << 32) | lo);
+        };
         auto load_k = [&](int pg0, int pg1) {
-            const uint16_t* k0 = kh + (size_t)pg0 * p.page_stride;
-            const uint16_t* k1 = kh + (size_t)pg1 * p.page_stride;
+            const gbytes k0 = page_base(kh, pg0) + klane;
+            const gbytes k1 = page_base(kh, pg1) + klane;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k0 + klane + kstep * s)));
-                tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k1 + klane + kstep * s)));
+                tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((gvec)(k0 + kstep * s)));
+                tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((gvec)(k1 + kstep * s)));
             }
         };
         auto load_v = [&](int pg0, int pg1) {
-            const uint16_t* v0 = vhp + (size_t)pg0 * p.page_stride;
-            const uint16_t* v1 = vhp + (size_t)pg1 * p.page_stride;
+            const gbytes v0 = page_base(vhp, pg0) + vlane;
+            const gbytes v1 = page_base(vhp, pg1) + vlane;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tv[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v0 + j * p.token_stride + vlane));
-                tv[4 + j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v1 + j * p.token_stride + vlane));
+                tv[j] = __builtin_nontemporal_load((gvec)(v0 + j * vstep));
+                tv[4 + j] = __builtin_nontemporal_load((gvec)(v1 + j * vstep));
             }
         };
 
@@ -344,12 +358,21 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const bool first_of_slice = i == 0;
             const int ctx = min(ctx_lens[b], p.max_pages * 16);
             const int item_first_kt = kt;
-            f32x4 oacc[8][NB];
-            float mref[NB], lsum[NB];
+            // Per sixteen-row block: output accumulators, the denominators (accumulated by the matrix unit as the
+            // product of the weights with a matrix of ones: all four entries of a lane hold its row's sum over the
+            // whole tile), the reference exponent, and two values derived from it that the tile loop uses in its
+            // place: the score above which the reference has to be raised, and the addend of the exponent.
+            f32x4 oacc[8][NB], lacc[NB];
+            float mref[NB], over[NB], nref[NB];
+            auto set_ref = [&](int nb, float m) {
+                mref[nb] = m;
+                over[nb] = (m + kRescaleSlack) / cs;            // -inf while the row has seen no key
+                nref[nb] = (m == -INFINITY) ? 0.f : -m;
+            };
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                mref[nb] = -INFINITY;
-                lsum[nb] = 0.f;
+                set_ref(nb, -INFINITY);
+                lacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) oacc[e][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -364,7 +387,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             // stay in accumulation registers; with the rescale inside the loop they were copied out to vector
             // registers at the top of every tile.
             f32x4 sacc[NB][2];
-            float lmax[NB];
+            float smax[NB];   // largest raw score of this lane's eight entries per block
             auto scores = [&](int tb) {
                 asm volatile("" ::: "memory");   // Q comes out of LDS anew for every tile instead of staying in registers
                 // ---- St = K Qt ----
@@ -401,10 +424,12 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 bool overshoot = false;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), fmaxf(sacc[nb][0][2], sacc[nb][0][3]));
-                    mx = fmaxf(mx, fmaxf(fmaxf(sacc[nb][1][0], sacc[nb][1][1]), fmaxf(sacc[nb][1][2], sacc[nb][1][3])));
-                    lmax[nb] = mx * cs;
-                    overshoot |= lmax[nb] > mref[nb] + kRescaleSlack;
+                    // chains of three-operand maxima
+                    float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), sacc[nb][0][2]);
+                    mx = fmaxf(fmaxf(mx, sacc[nb][0][3]), sacc[nb][1][0]);
+                    mx = fmaxf(fmaxf(mx, sacc[nb][1][1]), sacc[nb][1][2]);
+                    smax[nb] = fmaxf(mx, sacc[nb][1][3]);
+                    overshoot |= smax[nb] > over[nb];
                 }
                 return __any(overshoot) != 0;
             };
@@ -412,7 +437,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             auto row_max = [&](float (&rm)[NB]) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    float x = lmax[nb];
+                    float x = smax[nb] * cs;
                     x = fmaxf(x, __shfl_xor(x, 16));
                     rm[nb] = fmaxf(x, __shfl_xor(x, 32));
                 }
@@ -420,19 +445,16 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             auto weights_and_values = [&]() {
                 // ---- Pt = 2^(St*scale - ref), packed straight into B-operand order ----
                 bf16x8 pt[NB];
+                const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const float mr = (mref[nb] == -INFINITY) ? 0.f : mref[nb];
-                    float sum = 0.f;
 #pragma unroll
                     for (int tblk = 0; tblk < 2; ++tblk)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float pv = fast_exp2(fmaf(sacc[nb][tblk][j], cs, -mr));
-                            sum += pv;
-                            pt[nb][4 * tblk + j] = (__bf16)pv;
-                        }
-                    lsum[nb] += sum;
+                        for (int j = 0; j < 4; ++j)
+                            pt[nb][4 * tblk + j] = (__bf16)fast_exp2(fmaf(sacc[nb][tblk][j], cs, nref[nb]));
+                    // the denominator is the sum of the weights as the second product sees them (rounded)
+                    lacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pt[nb], lacc[nb], 0, 0, 0);
                 }
                 // ---- Vt: transpose the lane's 8 tokens x 8 dims, then Ot += Vt Pt ----
 #pragma unroll
@@ -470,7 +492,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                         for (int nb = 0; nb < NB; ++nb) {
                             const bool fresh = mref[nb] == -INFINITY;
                             late |= !fresh && rm[nb] > mref[nb] + kRescaleSlack;
-                            mref[nb] = fresh ? rm[nb] : mref[nb];
+                            set_ref(nb, fresh ? rm[nb] : mref[nb]);
                         }
                         if (__any(late)) { rescale = true; break; }
                     }
@@ -483,10 +505,10 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     for (int nb = 0; nb < NB; ++nb) {
                         const float mnew = fmaxf(mref[nb], rm[nb]);
                         const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
-                        lsum[nb] *= alpha;
+                        lacc[nb] *= alpha;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
-                        mref[nb] = mnew;
+                        set_ref(nb, mnew);
                     }
                     weights_and_values();
                     ++t; ++i;
@@ -515,10 +537,9 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 if (!complete && stash_slot >= 0) flush_stash(stash_slot);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    // denominators: add the four lanes (g = 0..3) that share a row
-                    float l = lsum[nb];
-                    l += __shfl_xor(l, 16);
-                    l += __shfl_xor(l, 32);
+                    // denominator of this lane's row (already summed over the tile's 32 keys, hence over the four lanes
+                    // that share the row)
+                    const float l = lacc[nb][0];
                     if (complete) {
                         // Every store instruction should write whole 128-byte lines.  Lane (row n, group
                         // g) holds dims 32g + 8j + e as four 16-byte chunks j.  A 4x4 transpose between
@@ -820,6 +841,31 @@ static void row_tiling(int M, int* NB, int* RG)
     else { *NB = 4; *RG = 4; }
 }
 
+// Launches the main kernel of one page layout for NB sixteen-row blocks per wavefront.  The dynamic LDS
+// of the larger variants is beyond the default 64 KB limit and has to be granted first.
+template <int NB, int LAYOUT>
+static int launch_main_nb(int W, size_t shmem, hipStream_t st, const AttnParams& p, const int32_t* block_table,
+                          const int32_t* ctx_lens)
+{
+    if (shmem > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<NB, LAYOUT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem) != hipSuccess) {
+        (void)hipGetLastError();
+        return IDLM_ERR_LAUNCH;
+    }
+    hipLaunchKernelGGL((isd_attention_bf16_kernel<NB, LAYOUT>), dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
+    return IDLM_OK;
+}
+
+template <int LAYOUT>
+static int launch_main(int NB, int W, size_t shmem, hipStream_t st, const AttnParams& p, const int32_t* block_table,
+                       const int32_t* ctx_lens)
+{
+    if (NB == 1) return launch_main_nb<1, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
+    if (NB == 2) return launch_main_nb<2, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
+    return launch_main_nb<4, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
+}
+
 }  // namespace idlm
 
 using namespace idlm;
@@ -922,7 +968,6 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.out = static_cast<uint16_t*>(out);
     p.B = B; p.S = S; p.Hq = Hq; p.Hkv = Hkv; p.G = G; p.M = S * G; p.max_pages = max_pages_per_seq;
     p.num_pages = num_pages;
-    p.k_operand_order = dtype == IDLM_DTYPE_BF16_KOP;
     p.RG = RG_;
     p.Mpad = 16 * NB;
     const size_t slots = (size_t)2 * W * 4;
@@ -935,20 +980,11 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     // per wavefront: Q operands of its current sequence, one parked partial result, that partial's row scalars
     const size_t shmem = (size_t)4 * NB * (4 * 64 * 16 * 2 + 16 * 16);
-    hipError_t attr = hipSuccess;
-    if (NB == 4)   // beyond the default 64 KB limit
-        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<4>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    else if (NB == 2)
-        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<2>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    if (attr != hipSuccess) {
-        (void)hipGetLastError();
-        return IDLM_ERR_LAUNCH;
-    }
-    if (NB == 1) hipLaunchKernelGGL(isd_attention_bf16_kernel<1>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
-    else if (NB == 2) hipLaunchKernelGGL(isd_attention_bf16_kernel<2>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
-    else hipLaunchKernelGGL(isd_attention_bf16_kernel<4>, dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
+    const int layout = dtype == IDLM_DTYPE_BF16_KOP ? 2 : (token_stride == 128 ? 1 : 0);
+    const int rc = layout == 2 ? launch_main<2>(NB, W, shmem, st, p, block_table, ctx_lens)
+                 : layout == 1 ? launch_main<1>(NB, W, shmem, st, p, block_table, ctx_lens)
+                               : launch_main<0>(NB, W, shmem, st, p, block_table, ctx_lens);
+    if (rc != IDLM_OK) return rc;
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const int VH = Hkv * p.RG, NW = W * 4;
     const int Wg = NW >= VH ? NW / VH : 1;   // slices per virtual head, as in the main kernel
