@@ -396,14 +396,22 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     sacc[nb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
                     sacc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
+                // The order of issue is pinned: kAhead Q operands are on their way from LDS before the first product
+                // starts and every pair of products is followed by the read of the operand kAhead pairs later, so
+                // that no product waits for LDS (left alone, the scheduler reads each operand right before its use).
+                constexpr int kOps = NB * 4, kAhead = 4;
+                bf16x8 qb[kOps];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
+                for (int r = 0; r < kAhead; ++r) qb[r] = __builtin_bit_cast(bf16x8, qlds[r * 64]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        const bf16x8 qb = __builtin_bit_cast(bf16x8, qlds[(nb * 4 + s) * 64]);
-                        sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][s], qb, sacc[nb][0], 0, 0, 0);
-                        sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][s], qb, sacc[nb][1], 0, 0, 0);
-                    }
+                for (int r = 0; r < kOps; ++r) {
+                    const int nb = r >> 2, ks = r & 3;
+                    sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][ks], qb[r], sacc[nb][0], 0, 0, 0);
+                    sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][ks], qb[r], sacc[nb][1], 0, 0, 0);
+                    if (r + kAhead < kOps) qb[r + kAhead] = __builtin_bit_cast(bf16x8, qlds[(r + kAhead) * 64]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 load_k(npg0, npg1);   // K registers are free again: next tile's K goes in flight
                 // ---- causal mask and end of context: only tiles that reach the stride's own rows ----
                 if (tb + 32 > ctx - S + 1) {
