@@ -203,8 +203,11 @@ __device__ __forceinline__ uint4 philox4x32_10(uint4 ctr, uint2 key)
 {
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, ctr.x), lo0 = 0xD2511F53u * ctr.x;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, ctr.z), lo1 = 0xCD9E8D57u * ctr.z;
+        // one 32 x 32 -> 64 bit multiply-add instruction per product instead of separate high and low multiplies
+        const unsigned long long p0 = (unsigned long long)0xD2511F53u * ctr.x;
+        const unsigned long long p1 = (unsigned long long)0xCD9E8D57u * ctr.z;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         ctr = make_uint4(hi1 ^ ctr.y ^ key.x, lo1, hi0 ^ ctr.w ^ key.y, lo0);
         key.x += 0x9E3779B9u;
         key.y += 0xBB67AE85u;
@@ -262,11 +265,13 @@ static inline AcceptPlan make_plan(int32_t B, int32_t S, int32_t V)
 {
     AcceptPlan p;
     const int64_t rows = (int64_t)B * S;
-    // A workgroup streams a whole row when there are enough rows to fill the chip (every extra
-    // slice costs a block reduction and a launch slot: whole rows measured 6.5 TB/s, 128 KB
-    // slices 5.7 TB/s on B*S = 4096 rows); fewer rows are cut into slices of at least 4K
-    // elements until about 4096 workgroups exist.
-    int64_t nsplit = (4096 + rows - 1) / (rows > 0 ? rows : 1);
+    // One round of about two workgroups per compute unit (512 on this part) is what streams fastest: a
+    // workgroup keeps 64 KB in flight, every further slice of a row costs a block reduction, and a launch
+    // of more workgroups than can be resident ends in a round of stragglers.  So a workgroup streams a
+    // whole row from about 400 rows on, and fewer rows are cut into round(512 / rows) slices (measured on
+    // 152K-element rows: 512 rows 54 us whole against 65 us in eight slices; 1024 rows 100 against 112 us
+    // in four; 128 rows best in four slices, 256 rows in two).
+    int64_t nsplit = rows > 0 ? (512 + rows / 2) / rows : 1;
     int64_t max_split = ((int64_t)V + 4095) / 4096;
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit < 1) nsplit = 1;
