@@ -461,6 +461,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="serve256")
     ap.add_argument("--stride", type=int, default=0, help="override the workload's S (the long32k stride sweep)")
+    ap.add_argument("--head-dim", type=int, default=0, help="override the workload's head dimension (64 or 128)")
     ap.add_argument("--workgroups", type=int, default=0, help="persistent attention grid (0 = one per CU)")
     ap.add_argument("--cpu-sample", type=int, default=256, help="sequences given to the CPU oracle (0 = skip)")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the CPU oracle (0 = all the box gives it)")
@@ -484,7 +485,8 @@ def main():
     from isd_inputs import get_config
     from isd_inputs.configs import LONG32K_STRIDES
 
-    cfg = get_config(args.workload, **({"S": args.stride} if args.stride else {}))
+    cfg = get_config(args.workload, **({"S": args.stride} if args.stride else {}),
+                     **({"D": args.head_dim} if args.head_dim else {}))
     dev = "cuda:0"
     torch.cuda.set_device(0)
     hev = HipEvents()
@@ -592,7 +594,7 @@ def main():
             kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / line["stream_ceiling"]["read_GBps"]
     if "cpu" in sections and args.cpu_sample > 0:
         line["cpu_baseline"] = cpu_baseline(case.att, case.acc, cfg, min(args.cpu_sample, B), args.cpu_threads)
-    if "configs" in sections and args.workload == "serve256" and not args.stride:
+    if "configs" in sections and args.workload == "serve256" and not args.stride and not args.head_dim:
         del case
         torch.cuda.empty_cache()
         configs = {}
@@ -600,6 +602,8 @@ def main():
             for s_ in strides:
                 c = get_config(name, **({"S": s_} if s_ else {}))
                 configs[name + ("_S%d" % s_ if s_ else "")] = config_line(name, c, dev, hev, stream)
+        # the 8B-class step with 64-wide heads (half the K/V bytes per token): the same kernels, other head dimension
+        configs["8b_D64"] = config_line("8b", get_config("8b", D=64), dev, hev, stream)
         line["configs"] = configs
     print(json.dumps(line))
 

@@ -92,10 +92,10 @@ enum {
  * block_table int32 [B,max_pages_per_seq].
  * ctx_lens    int32 [B]: KV length of each sequence INCLUDING this step's S rows.
  * scale       softmax scale; <= 0 selects 1/sqrt(D).
- * dtype       IDLM_DTYPE_BF16 / IDLM_DTYPE_BF16_KOP at D = 128 (MFMA path; fp32 accumulation; G = Hq/Hkv
- *             and S with S*G <= 256), or the plain path, one wavefront per (row, head) with fp32
- *             arithmetic, for correctness rather than speed: IDLM_DTYPE_F32 with D in {64,128} and
- *             IDLM_DTYPE_BF16 with D = 64.
+ * dtype       IDLM_DTYPE_BF16 with D in {64,128}, IDLM_DTYPE_BF16_KOP with D = 128 (MFMA path; fp32
+ *             accumulation; G = Hq/Hkv and S with S*G <= 256), or IDLM_DTYPE_F32 with D in {64,128}
+ *             (plain path, one wavefront per (row, head) with fp32 arithmetic, for correctness
+ *             rather than speed).
  * num_workgroups  size of the persistent grid that shares the batch's 32-token tiles evenly;
  *             0 = one workgroup per compute unit of the current device (at most 256), fewer when B and the
  *             width of the block table bound the work to a few tiles per wavefront (the setting to use);
@@ -115,8 +115,8 @@ int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
 
 /* Bytes of workspace idlm_isd_attention needs for these shapes and this num_workgroups (the value
  * that will be passed to the call; 0 = the library's own choice, at most 256 workgroups): two
- * partial-result slots per wavefront of the grid, 35 MB for the default grid at S*G >= 33 query
- * rows per KV head.  Host-only, no GPU needed.  Returns 0 for shapes that are rejected anyway. */
+ * partial-result slots per wavefront of the grid, 35 MB for the default grid at D = 128 and
+ * S*G >= 33 query rows per KV head.  Host-only, no GPU needed.  Returns 0 for shapes that are rejected anyway. */
 size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
                                     int32_t P, int32_t max_pages_per_seq, int32_t dtype,
                                     int32_t num_workgroups);

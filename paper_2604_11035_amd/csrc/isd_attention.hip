@@ -35,6 +35,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
 constexpr int kMaxWorkgroups = 1024;      // upper bound of a forced persistent grid
@@ -45,8 +47,8 @@ struct AttnParams {
     const uint16_t* k;
     const uint16_t* v;
     uint16_t* out;
-    u32x4* ws_o;    // [2*NW][NB][4][64] partial outputs of a slot (2v: first sequence of wavefront v's slice, 2v+1: its
-                    //                   last): eight fp16 per entry, normalised per row to a largest magnitude of 1
+    void* ws_o;     // [2*NW][NB][4][64] partial outputs of a slot (2v: first sequence of wavefront v's slice, 2v+1: its
+                    //                   last): D/16 fp16 per entry, normalised per row to a largest magnitude of 1
     f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator l, largest magnitude of O / l, unused
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
     int num_pages;
@@ -72,15 +74,6 @@ struct TilePlan {     // static LDS of both kernels
     int incl[256];    // inclusive prefix sums of the per-thread sequence weights
     int wave_sum[4];  // weight counted by each of the block's four wavefronts
 };
-
-// Copies one accumulation register to an ordinary vector register at exactly this point of the
-// program (the compiler neither hoists nor batches it).
-__device__ __forceinline__ float acc_read(float a)
-{
-    float v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
-    return v;
-}
 
 // The value of x, hidden from the optimiser: what is computed from it is computed here and now
 // instead of once, ahead of the loops, and then kept in (or spilled from) a register.
@@ -202,12 +195,22 @@ __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32
 // LAYOUT fixes the strides inside a page at compile time, so that the eight loads of an operand share
 // one address and differ in their immediate offsets: 0 = any strides (token-major pools, padded rows),
 // 1 = contiguous slot-major pages (token_stride = 128), 2 = the same with the K pages in operand order.
-template <int NB, int LAYOUT>
+//
+// D is the head dimension, 64 or 128: D/32 contraction steps for St, D/16 sixteen-row blocks of Ot, and a lane's
+// share of a V row (and of an output row) is a chunk of D/16 consecutive values, 8 or 16 bytes.
+template <int D> struct LaneChunk;
+template <> struct LaneChunk<128> { typedef u32x4 type; };
+template <> struct LaneChunk<64> { typedef u32x2 type; };
+
+template <int NB, int LAYOUT, int D>
 __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParams p,
                                                                  const int32_t* __restrict__ block_table,
                                                                  const int32_t* __restrict__ ctx_lens)
 {
-    extern __shared__ u32x4 qlds_all[];   // [wavefront][(nb*4 + s)*64 + lane] Q operands of the current item
+    constexpr int KS = D / 32;    // contraction steps of St = K Qt
+    constexpr int E = D / 16;     // sixteen-row blocks of Ot = values per lane chunk
+    typedef typename LaneChunk<D>::type chunk_t;
+    extern __shared__ u32x4 qlds_all[];   // [wavefront][(nb*KS + s)*64 + lane] Q operands of the current item
     __shared__ TilePlan plan;
 
     const int total_weight = plan_scan(p, ctx_lens, plan);
@@ -232,12 +235,13 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     const int n = lane & 15, g = lane >> 4;
     const int S = p.S, G = p.G, M = p.M;
     const float cs = p.scale_log2;
-    u32x4* const qlds = qlds_all + (size_t)w * (NB * 4 * 64) + lane;
+    u32x4* const qlds = qlds_all + (size_t)w * (NB * KS * 64) + lane;
     // a partial result waits here, in this wavefront's own LDS, until the wavefront has read all its K/V
-    u32x4* const stash_o = qlds_all + (size_t)(4 + w) * (NB * 4 * 64);
-    f32x4* const stash_ml = reinterpret_cast<f32x4*>(qlds_all + (size_t)8 * (NB * 4 * 64)) + w * (NB * 16);
+    chunk_t* const stash_o = reinterpret_cast<chunk_t*>(qlds_all + (size_t)4 * (NB * KS * 64)) + (size_t)w * (NB * 4 * 64);
+    f32x4* const stash_ml = reinterpret_cast<f32x4*>(reinterpret_cast<chunk_t*>(qlds_all + (size_t)4 * (NB * KS * 64)) +
+                                                     (size_t)4 * (NB * 4 * 64)) + w * (NB * 16);
     auto flush_stash = [&](int slot) {
-        u32x4* dst = p.ws_o + (size_t)slot * (NB * 4 * 64) + lane;
+        chunk_t* dst = static_cast<chunk_t*>(p.ws_o) + (size_t)slot * (NB * 4 * 64) + lane;
 #pragma unroll
         for (int q = 0; q < NB * 4; ++q) dst[q * 64] = stash_o[q * 64 + lane];
         if (lane < NB * 16) p.ws_ml[(size_t)slot * (NB * 16) + lane] = stash_ml[lane];
@@ -271,8 +275,8 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 do { ++b; nt = seq_tiles(p, ctx_lens, b); } while (nt == 0);
             }
         };
-        bf16x8 tk[2][4];   // K of the current tile: [16-token block][k-step], A operand of St
-        u32x4 tv[8];       // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims 8*n .. 8*n+7
+        bf16x8 tk[2][KS];  // K of the current tile: [16-token block][k-step], A operand of St
+        chunk_t tv[8];     // V of the current tile: slot j' = token 16*(j'/4) + 4*g + j'%4, dims E*n .. E*n+E-1
         // Addresses are a wave-uniform 64-bit page base (scalar registers) plus a 32-bit lane offset in bytes
         // (the host checks that it fits) plus, for the fixed layouts, an immediate: one address per operand and
         // page instead of one per load.
@@ -280,10 +284,11 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         // page's 4 KB block, so a load instruction reads 1 KB of whole cache lines instead of 16 rows x 64 bytes
         typedef const __attribute__((address_space(1))) char* gbytes;
         typedef const __attribute__((address_space(1))) u32x4* gvec;
-        const int tstride = LAYOUT == 0 ? (int)p.token_stride : 128;
+        typedef const __attribute__((address_space(1))) chunk_t* gchunk;
+        const int tstride = LAYOUT == 0 ? (int)p.token_stride : D;
         const uint32_t klane = LAYOUT == 2 ? (uint32_t)(lane * 16) : (uint32_t)(2 * (n * tstride + g * 8));
         const int kstep = LAYOUT == 2 ? 1024 : 64;
-        const uint32_t vlane = (uint32_t)(2 * (4 * g * tstride + n * 8));
+        const uint32_t vlane = (uint32_t)(2 * (4 * g * tstride + n * E));
         const int vstep = 2 * tstride;
         auto page_base = [&](const uint16_t* pool, int pg) {
             const uint64_t a = reinterpret_cast<uint64_t>(pool) + 2 * (uint64_t)pg * (uint64_t)p.page_stride;
@@ -295,7 +300,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const gbytes k0 = page_base(kh, pg0) + klane;
             const gbytes k1 = page_base(kh, pg1) + klane;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < KS; ++s) {
                 tk[0][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((gvec)(k0 + kstep * s)));
                 tk[1][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((gvec)(k1 + kstep * s)));
             }
@@ -305,8 +310,8 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             const gbytes v1 = page_base(vhp, pg1) + vlane;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tv[j] = __builtin_nontemporal_load((gvec)(v0 + j * vstep));
-                tv[4 + j] = __builtin_nontemporal_load((gvec)(v1 + j * vstep));
+                tv[j] = __builtin_nontemporal_load((gchunk)(v0 + j * vstep));
+                tv[4 + j] = __builtin_nontemporal_load((gchunk)(v1 + j * vstep));
             }
         };
 
@@ -327,16 +332,16 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
 
         // Q rows of sequence bq for this lane (row n of each 16-row block, dims 32s + 8g .. +7); rows
         // past the stride's last one read its last row instead and are zeroed on the way to LDS
-        u32x4 qreg[NB][4];
+        u32x4 qreg[NB][KS];
         auto load_q = [&](int bq) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int row = opaque(rowbase + 16 * nb + n);
                 const int qi = row < M ? qpos[nb] : S - 1;
                 const int gq = row < M ? row - qpos[nb] * G : G - 1;
-                const uint16_t* qp = p.q + ((size_t)(bq * S + qi) * p.Hq + kvh * G + gq) * 128 + g * 8;
+                const uint16_t* qp = p.q + ((size_t)(bq * S + qi) * p.Hq + kvh * G + gq) * D + g * 8;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) qreg[nb][s] = *reinterpret_cast<const u32x4*>(qp + 32 * s);
+                for (int s = 0; s < KS; ++s) qreg[nb][s] = *reinterpret_cast<const u32x4*>(qp + 32 * s);
             }
         };
         auto store_q = [&]() {
@@ -344,7 +349,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             for (int nb = 0; nb < NB; ++nb) {
                 const bool valid = opaque(rowbase + 16 * nb + n) < M;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) qlds[(nb * 4 + s) * 64] = valid ? qreg[nb][s] : u32x4{0u, 0u, 0u, 0u};
+                for (int s = 0; s < KS; ++s) qlds[(nb * KS + s) * 64] = valid ? qreg[nb][s] : u32x4{0u, 0u, 0u, 0u};
             }
         };
         load_q(b);
@@ -362,7 +367,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
             // product of the weights with a matrix of ones: all four entries of a lane hold its row's sum over the
             // whole tile), the reference exponent, and two values derived from it that the tile loop uses in its
             // place: the score above which the reference has to be raised, and the addend of the exponent.
-            f32x4 oacc[8][NB], lacc[NB];
+            f32x4 oacc[E][NB], lacc[NB];
             float mref[NB], over[NB], nref[NB];
             auto set_ref = [&](int nb, float m) {
                 mref[nb] = m;
@@ -374,7 +379,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 set_ref(nb, -INFINITY);
                 lacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) oacc[e][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int e = 0; e < E; ++e) oacc[e][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
             int pb = b, pkt = kt, pnt = nt;   // cursor of the tile after this sequence's last one
 
@@ -399,14 +404,14 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 // The order of issue is pinned: kAhead Q operands are on their way from LDS before the first product
                 // starts and every pair of products is followed by the read of the operand kAhead pairs later, so
                 // that no product waits for LDS (left alone, the scheduler reads each operand right before its use).
-                constexpr int kOps = NB * 4, kAhead = 4;
+                constexpr int kOps = NB * KS, kAhead = kOps < 4 ? kOps : 4;
                 bf16x8 qb[kOps];
 #pragma unroll
                 for (int r = 0; r < kAhead; ++r) qb[r] = __builtin_bit_cast(bf16x8, qlds[r * 64]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < kOps; ++r) {
-                    const int nb = r >> 2, ks = r & 3;
+                    const int nb = r / KS, ks = r % KS;
                     sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][ks], qb[r], sacc[nb][0], 0, 0, 0);
                     sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][ks], qb[r], sacc[nb][1], 0, 0, 0);
                     if (r + kAhead < kOps) qb[r + kAhead] = __builtin_bit_cast(bf16x8, qlds[(r + kAhead) * 64]);
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     // value rows beyond the context may hold anything (NaN included): zero them
 #pragma unroll
                     for (int jj = 0; jj < 8; ++jj)
-                        if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) tv[jj] = u32x4{0u, 0u, 0u, 0u};
+                        if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) tv[jj] = chunk_t(0u);
                 }
                 bool overshoot = false;
 #pragma unroll
@@ -464,9 +469,9 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     // the denominator is the sum of the weights as the second product sees them (rounded)
                     lacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pt[nb], lacc[nb], 0, 0, 0);
                 }
-                // ---- Vt: transpose the lane's 8 tokens x 8 dims, then Ot += Vt Pt ----
+                // ---- Vt: transpose the lane's 8 tokens x E dims, then Ot += Vt Pt ----
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < E; ++e) {
                     u32x4 vt;
 #pragma unroll
                     for (int wp = 0; wp < 4; ++wp) {
@@ -515,7 +520,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                         const float alpha = (mnew == -INFINITY) ? 1.f : fast_exp2(mref[nb] - mnew);
                         lacc[nb] *= alpha;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) oacc[e][nb] *= alpha;
+                        for (int e = 0; e < E; ++e) oacc[e][nb] *= alpha;
                         set_ref(nb, mnew);
                     }
                     weights_and_values();
@@ -532,12 +537,6 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 const bool complete = item_first_kt == 0 && kt + n_in == nt;
                 const size_t wslot = (size_t)(2 * wv + (first_of_slice ? 0 : 1));
                 const int q4 = n & 3;
-                // The accumulators sit in accumulation registers, which vector ALU instructions cannot
-                // read; they are copied out sixteen-row block by block right where they are used
-                // (left to itself the compiler copies all of them out at once and then runs out of
-                // registers, and the reloads of what it spilled drain the memory counter between the
-                // stores).  An MFMA result needs up to 18 idle cycles before such a copy may read it.
-                asm volatile("s_nop 15\n\ts_nop 15");
                 // Stores that mix into the stream of K/V reads cost several times their share of the bytes
                 // (the memory goes back and forth between reading and writing), so a partial result is
                 // kept in LDS and written when the wavefront has no more K/V to read: the first sequence's
@@ -550,17 +549,19 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     const float l = lacc[nb][0];
                     if (complete) {
                         // Every store instruction should write whole 128-byte lines.  Lane (row n, group
-                        // g) holds dims 32g + 8j + e as four 16-byte chunks j.  A 4x4 transpose between
+                        // g) holds dims 4E g + E j + e as four chunks j of E values.  A 4x4 transpose between
                         // j and the four lanes of a quad leaves lane (n, g) with chunk 4g + n%4 of rows
-                        // 4*(n/4) + j: store j then writes four complete 256-byte rows.
+                        // 4*(n/4) + j: store j then writes four complete rows of 2 D bytes.
                         const float inv = 1.f / l;
-                        u32x4 c[4];
+                        chunk_t c[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            bf16x8 o;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc_read(oacc[e][nb][j]) * inv);
-                            c[j] = __builtin_bit_cast(u32x4, o);
+                            for (int e = 0; e < E; e += 2) {
+                                typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+                                const bf16x2 o2 = {(__bf16)(oacc[e][nb][j] * inv), (__bf16)(oacc[e + 1][nb][j] * inv)};
+                                c[j][e >> 1] = __builtin_bit_cast(uint32_t, o2);
+                            }
                         }
 #pragma unroll
                         for (int stage = 1; stage <= 2; ++stage) {
@@ -569,13 +570,13 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                             for (int pair = 0; pair < 2; ++pair) {
                                 // stage 1 swaps chunks (0,1) and (2,3) with lane^1, stage 2 (0,2) and (1,3) with lane^2
                                 const int lo_i = stage == 1 ? 2 * pair : pair, hi_i = lo_i + stage;
-                                u32x4 send, recv;
+                                chunk_t send, recv;
 #pragma unroll
-                                for (int k = 0; k < 4; ++k) send[k] = hi ? c[lo_i][k] : c[hi_i][k];
+                                for (int k = 0; k < E / 2; ++k) send[k] = hi ? c[lo_i][k] : c[hi_i][k];
 #pragma unroll
-                                for (int k = 0; k < 4; ++k) recv[k] = __shfl_xor(send[k], stage);
+                                for (int k = 0; k < E / 2; ++k) recv[k] = __shfl_xor(send[k], stage);
 #pragma unroll
-                                for (int k = 0; k < 4; ++k) {
+                                for (int k = 0; k < E / 2; ++k) {
                                     if (hi) c[lo_i][k] = recv[k]; else c[hi_i][k] = recv[k];
                                 }
                             }
@@ -585,32 +586,32 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             if (row0 + j < M) {
-                                uint16_t* op = p.out + ((size_t)(b * S + ip) * p.Hq + kvh * G + gq) * 128 + (4 * g + q4) * 8;
-                                __builtin_nontemporal_store(c[j], reinterpret_cast<u32x4*>(op));
+                                uint16_t* op = p.out + ((size_t)(b * S + ip) * p.Hq + kvh * G + gq) * D + (4 * g + q4) * E;
+                                __builtin_nontemporal_store(c[j], reinterpret_cast<chunk_t*>(op));
                             }
                             if (++gq == G) { gq = 0; ++ip; }
                         }
                     } else {
                         // partial: each row scaled to a largest magnitude of 1 and kept as fp16, [nb][j][lane]
-                        // entries of dims 32g + 8j .. +7 of local row 16nb + n (the merge kernel's unit of work)
-                        float vals[8][4];
+                        // entries of dims 4E g + E j .. + E-1 of local row 16nb + n (the merge kernel's unit of work)
                         float amax = 0.f;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
+                        for (int e = 0; e < E; ++e)
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                vals[e][j] = acc_read(oacc[e][nb][j]);
-                                amax = fmaxf(amax, fabsf(vals[e][j]));
-                            }
+                            for (int j = 0; j < 4; ++j) amax = fmaxf(amax, fabsf(oacc[e][nb][j]));
                         amax = fmaxf(amax, __shfl_xor(amax, 16));
                         amax = fmaxf(amax, __shfl_xor(amax, 32));
                         const float inv = amax > 0.f ? 1.f / amax : 0.f;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            f16x8 hv;
+                            chunk_t hv;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) hv[e] = (_Float16)(vals[e][j] * inv);
-                            stash_o[(nb * 4 + j) * 64 + lane] = __builtin_bit_cast(u32x4, hv);
+                            for (int e = 0; e < E; e += 2) {
+                                typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+                                const f16x2 h2 = {(_Float16)(oacc[e][nb][j] * inv), (_Float16)(oacc[e + 1][nb][j] * inv)};
+                                hv[e >> 1] = __builtin_bit_cast(uint32_t, h2);
+                            }
+                            stash_o[(nb * 4 + j) * 64 + lane] = hv;
                         }
                         // l > 0 whenever the row saw a key; the merge kernel skips rows whose reference is -inf
                         if (g == 0) stash_ml[nb * 16 + n] = f32x4{mref[nb], l, l > 0.f ? amax / l : 0.f, 0.f};
@@ -629,6 +630,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
 // cut between slices j-1 and j of virtual head vh (the main kernel's partition); the block of the
 // first cut that falls inside a sequence merges all of that sequence's partials:
 // out = sum_k 2^(m_k - m*) O_k / sum_k 2^(m_k - m*) l_k.
+template <int D>
 __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnParams p, int Wg, int rows_per_group,
                                                                   const int32_t* __restrict__ ctx_lens)
 {
@@ -657,21 +659,24 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int kvh = vh / p.RG;
     const int rowbase = (vh - kvh * p.RG) * rows_per_group;
     const int nrows = min(rows_per_group, p.M - rowbase);
-    // partial layout: [slot][nb][j][lane = 16g+n] entries of eight fp16 = dims 32g + 8j .. +7 of local
+    // partial layout: [slot][nb][j][lane = 16g+n] entries of E = D/16 fp16 = dims 4E g + E j .. + E-1 of local
     // row 16nb + n, each row scaled to a largest magnitude of 1; (reference exponent, denominator,
-    // scale) at [slot][nb][n].  Thread (lane, j) handles one entry of every 16-row block: 16-byte
-    // loads contiguous across threads, one 16-byte store, and one pass with a running reference
-    // keeps a single round trip per partial.
+    // scale) at [slot][nb][n].  Thread (lane, j) handles one entry of every 16-row block: loads
+    // contiguous across threads, one store, and one pass with a running reference keeps a single
+    // round trip per partial.
+    constexpr int E = D / 16;
+    typedef typename LaneChunk<D>::type chunk_t;
+    const chunk_t* const ws_o = static_cast<const chunk_t*>(p.ws_o);
     const int NBk = rows_per_group >> 4;
     const int j = threadIdx.x & 3, lane = threadIdx.x >> 2;
     const int n = lane & 15, g = lane >> 4;
-    float acc[4][8], mrun[4], den[4];
+    float acc[4][E], mrun[4], den[4];
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb) {
         mrun[nb] = -INFINITY;
         den[nb] = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[nb][e] = 0.f;
+        for (int e = 0; e < E; ++e) acc[nb][e] = 0.f;
     }
     int knext = first_begin;                       // slice k is [kbeg, kend); slice jcut starts at the cut
     for (int k = jcut - 1; k < Wg; ++k) {
@@ -682,13 +687,13 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
         if (kbeg == kend) continue;
         const size_t slot = (size_t)slot_of(k, kbeg);
         f32x4 ml[4];
-        u32x4 o[4];
+        chunk_t o[4];
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
             if (nb < NBk) {
                 const size_t sl = slot * NBk + nb;
                 ml[nb] = p.ws_ml[sl * 16 + n];
-                o[nb] = p.ws_o[(sl * 4 + j) * 64 + lane];
+                o[nb] = ws_o[(sl * 4 + j) * 64 + lane];
             }
         }
 #pragma unroll
@@ -699,9 +704,10 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
                 const float anew = fast_exp2(ml[nb][0] - mnew);
                 den[nb] = den[nb] * aold + ml[nb][1] * anew;
                 const float wo = anew * ml[nb][1] * ml[nb][2];
-                const f16x8 hv = __builtin_bit_cast(f16x8, o[nb]);
+                typedef __attribute__((ext_vector_type(E))) _Float16 f16xE;
+                const f16xE hv = __builtin_bit_cast(f16xE, o[nb]);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[nb][e] = acc[nb][e] * aold + (float)hv[e] * wo;
+                for (int e = 0; e < E; ++e) acc[nb][e] = acc[nb][e] * aold + (float)hv[e] * wo;
                 mrun[nb] = mnew;
             }
         }
@@ -713,17 +719,18 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
             const float inv = 1.f / den[nb];
             const int row = rowbase + lrow;
             const int i = row / p.G, gq = row - i * p.G;
-            bf16x8 ov;
+            typedef __attribute__((ext_vector_type(E))) __bf16 bf16xE;
+            bf16xE ov;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ov[e] = (__bf16)(acc[nb][e] * inv);
-            uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * 128 + 32 * g + 8 * j;
-            *reinterpret_cast<bf16x8*>(op) = ov;
+            for (int e = 0; e < E; ++e) ov[e] = (__bf16)(acc[nb][e] * inv);
+            uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * D + 4 * E * g + E * j;
+            *reinterpret_cast<bf16xE*>(op) = ov;
         }
     }
 }
 
-// ---- plain path (fp32, and bf16 at D = 64; small correctness configurations): one wavefront per
-// (sequence, row, head), fp32 arithmetic ----
+// ---- plain path (fp32; small correctness configurations): one wavefront per (sequence, row, head),
+// fp32 arithmetic ----
 struct AttnParamsF32 {
     const void* q;
     const void* k;
@@ -736,19 +743,7 @@ struct AttnParamsF32 {
     float scale_log2;
 };
 
-// four consecutive elements of a row as fp32 (bf16 widens exactly)
-template <bool BF16>
-__device__ __forceinline__ float4 load4(const void* base, size_t idx)
-{
-    if (BF16) {
-        const uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + idx);
-        return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
-                           __uint_as_float(r.y & 0xFFFF0000u));
-    }
-    return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + idx);
-}
-
-template <int D, bool BF16>
+template <int D>
 __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF32 p)
 {
     const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
@@ -768,8 +763,8 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
         float dot = 0.f;
 #pragma unroll
         for (int d = 0; d < D; d += 4) {
-            const float4 kk = load4<BF16>(p.k, off + d);
-            const float4 qq = load4<BF16>(p.q, qoff + d);
+            const float4 kk = *reinterpret_cast<const float4*>(static_cast<const float*>(p.k) + off + d);
+            const float4 qq = *reinterpret_cast<const float4*>(static_cast<const float*>(p.q) + qoff + d);
             dot += kk.x * qq.x + kk.y * qq.y + kk.z * qq.z + kk.w * qq.w;
         }
         const float s = dot * p.scale_log2;
@@ -779,7 +774,7 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
         l = l * alpha + pv;
 #pragma unroll
         for (int d = 0; d < D; d += 4) {
-            const float4 vv = load4<BF16>(p.v, off + d);
+            const float4 vv = *reinterpret_cast<const float4*>(static_cast<const float*>(p.v) + off + d);
             o[d] = o[d] * alpha + pv * vv.x;
             o[d + 1] = o[d + 1] * alpha + pv * vv.y;
             o[d + 2] = o[d + 2] * alpha + pv * vv.z;
@@ -801,22 +796,16 @@ __global__ __launch_bounds__(64) void isd_attention_f32_kernel(const AttnParamsF
     }
     if (lane == 0) {
         const float inv = 1.f / l;
-        if (BF16) {
-            __bf16* op = static_cast<__bf16*>(p.out) + qoff;
+        float* op = static_cast<float*>(p.out) + qoff;
 #pragma unroll
-            for (int d = 0; d < D; ++d) op[d] = (__bf16)(o[d] * inv);
-        } else {
-            float* op = static_cast<float*>(p.out) + qoff;
-#pragma unroll
-            for (int d = 0; d < D; ++d) op[d] = o[d] * inv;
-        }
+        for (int d = 0; d < D; ++d) op[d] = o[d] * inv;
     }
 }
 
 // ---- host side ----------------------------------------------------------------------------
 
-// bf16 at D = 128 runs on the MFMA kernels; fp32, and bf16 at D = 64, on the plain one
-static bool uses_mfma_path(int32_t D, int32_t dtype) { return dtype != IDLM_DTYPE_F32 && D == 128; }
+// bf16 (D = 64 or 128) runs on the MFMA kernels, fp32 on the plain one
+static bool uses_mfma_path(int32_t D, int32_t dtype) { return dtype != IDLM_DTYPE_F32 && (D == 64 || D == 128); }
 
 static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, int32_t P,
                       int32_t max_pages, int32_t dtype, int* err)
@@ -830,10 +819,10 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
         P != 16 || max_pages < 1 || (int64_t)max_pages * P >= (1 << 30) ||
         (int64_t)B * max_pages >= (1LL << 31)) { *err = IDLM_ERR_SHAPE; return false; }
     const int G = Hq / Hkv;
+    if ((D != 64 && D != 128) || (dtype == IDLM_DTYPE_BF16_KOP && D != 128)) { *err = IDLM_ERR_DTYPE; return false; }
     if (uses_mfma_path(D, dtype)) {
         if (S * G > 256) { *err = IDLM_ERR_SHAPE; return false; }
     } else {
-        if ((D != 64 && D != 128) || dtype == IDLM_DTYPE_BF16_KOP) { *err = IDLM_ERR_DTYPE; return false; }
         if (Hq > 65535) { *err = IDLM_ERR_SHAPE; return false; }
     }
     return true;
@@ -851,38 +840,39 @@ static void row_tiling(int M, int* NB, int* RG)
 
 // Launches the main kernel of one page layout for NB sixteen-row blocks per wavefront.  The dynamic LDS
 // of the larger variants is beyond the default 64 KB limit and has to be granted first.
-template <int NB, int LAYOUT>
+template <int NB, int LAYOUT, int D>
 static int launch_main_nb(int W, size_t shmem, hipStream_t st, const AttnParams& p, const int32_t* block_table,
                           const int32_t* ctx_lens)
 {
     if (shmem > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<NB, LAYOUT>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&isd_attention_bf16_kernel<NB, LAYOUT, D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem) != hipSuccess) {
         (void)hipGetLastError();
         return IDLM_ERR_LAUNCH;
     }
-    hipLaunchKernelGGL((isd_attention_bf16_kernel<NB, LAYOUT>), dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
+    hipLaunchKernelGGL((isd_attention_bf16_kernel<NB, LAYOUT, D>), dim3(W), dim3(256), shmem, st, p, block_table, ctx_lens);
     return IDLM_OK;
 }
 
-template <int LAYOUT>
+template <int LAYOUT, int D>
 static int launch_main(int NB, int W, size_t shmem, hipStream_t st, const AttnParams& p, const int32_t* block_table,
                        const int32_t* ctx_lens)
 {
-    if (NB == 1) return launch_main_nb<1, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
-    if (NB == 2) return launch_main_nb<2, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
-    return launch_main_nb<4, LAYOUT>(W, shmem, st, p, block_table, ctx_lens);
+    if (NB == 1) return launch_main_nb<1, LAYOUT, D>(W, shmem, st, p, block_table, ctx_lens);
+    if (NB == 2) return launch_main_nb<2, LAYOUT, D>(W, shmem, st, p, block_table, ctx_lens);
+    return launch_main_nb<4, LAYOUT, D>(W, shmem, st, p, block_table, ctx_lens);
 }
 
 }  // namespace idlm
 
 using namespace idlm;
 
-// bytes of the partial-result slots of a grid of W workgroups: two slots of 16*NB rows per wavefront
-static size_t partial_slots_bytes(int NB, int W)
+// bytes of the partial-result slots of a grid of W workgroups: two slots of 16*NB rows per wavefront, each row
+// as D fp16 values plus four fp32 row scalars
+static size_t partial_slots_bytes(int NB, int W, int D)
 {
     const size_t slots = (size_t)2 * W * 4;
-    return slots * NB * (4 * 64 * sizeof(u32x4) + 16 * sizeof(f32x4));
+    return slots * NB * (4 * 64 * (size_t)(D / 8) + 16 * sizeof(f32x4));
 }
 
 extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
@@ -895,7 +885,7 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
     if (!uses_mfma_path(D, dtype) || B == 0) return 0;
     int NB, RG;
     row_tiling(S * (Hq / Hkv), &NB, &RG);
-    return partial_slots_bytes(NB, num_workgroups ? num_workgroups : kDefaultWorkgroups);
+    return partial_slots_bytes(NB, num_workgroups ? num_workgroups : kDefaultWorkgroups, D);
 }
 
 extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
@@ -933,9 +923,8 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
         (void)hipGetLastError();
         dim3 grid(Hq, S, B);
         if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
-        if (dtype == IDLM_DTYPE_BF16) hipLaunchKernelGGL((isd_attention_f32_kernel<64, true>), grid, dim3(64), 0, st, p);
-        else if (D == 64) hipLaunchKernelGGL((isd_attention_f32_kernel<64, false>), grid, dim3(64), 0, st, p);
-        else hipLaunchKernelGGL((isd_attention_f32_kernel<128, false>), grid, dim3(64), 0, st, p);
+        if (D == 64) hipLaunchKernelGGL(isd_attention_f32_kernel<64>, grid, dim3(64), 0, st, p);
+        else hipLaunchKernelGGL(isd_attention_f32_kernel<128>, grid, dim3(64), 0, st, p);
         if (events) {
             (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
             (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
@@ -979,26 +968,30 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.RG = RG_;
     p.Mpad = 16 * NB;
     const size_t slots = (size_t)2 * W * 4;
-    p.ws_o = static_cast<u32x4*>(workspace);
-    p.ws_ml = reinterpret_cast<f32x4*>(p.ws_o + slots * NB * 4 * 64);
+    p.ws_o = workspace;
+    p.ws_ml = reinterpret_cast<f32x4*>(static_cast<char*>(workspace) + slots * NB * 4 * 64 * (size_t)(D / 8));
     p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
     p.scale_log2 = scale * kLog2e;
 
     (void)hipGetLastError();
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[0]), st);
     // per wavefront: Q operands of its current sequence, one parked partial result, that partial's row scalars
-    const size_t shmem = (size_t)4 * NB * (4 * 64 * 16 * 2 + 16 * 16);
-    const int layout = dtype == IDLM_DTYPE_BF16_KOP ? 2 : (token_stride == 128 ? 1 : 0);
-    const int rc = layout == 2 ? launch_main<2>(NB, W, shmem, st, p, block_table, ctx_lens)
-                 : layout == 1 ? launch_main<1>(NB, W, shmem, st, p, block_table, ctx_lens)
-                               : launch_main<0>(NB, W, shmem, st, p, block_table, ctx_lens);
+    const size_t shmem = (size_t)4 * NB * ((D / 32) * 64 * 16 + 4 * 64 * (D / 8) + 16 * 16);
+    const int layout = dtype == IDLM_DTYPE_BF16_KOP ? 2 : (token_stride == D ? 1 : 0);
+    const int rc = D == 64 ? (layout == 1 ? launch_main<1, 64>(NB, W, shmem, st, p, block_table, ctx_lens)
+                                          : launch_main<0, 64>(NB, W, shmem, st, p, block_table, ctx_lens))
+                 : layout == 2 ? launch_main<2, 128>(NB, W, shmem, st, p, block_table, ctx_lens)
+                 : layout == 1 ? launch_main<1, 128>(NB, W, shmem, st, p, block_table, ctx_lens)
+                               : launch_main<0, 128>(NB, W, shmem, st, p, block_table, ctx_lens);
     if (rc != IDLM_OK) return rc;
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
     const int VH = Hkv * p.RG, NW = W * 4;
     const int Wg = NW >= VH ? NW / VH : 1;   // slices per virtual head, as in the main kernel
-    if (Wg > 1)
-        hipLaunchKernelGGL(isd_attention_merge_kernel, dim3((unsigned)((Wg - 1) * VH)), dim3(256), 0, st, p, Wg,
-                           p.Mpad, ctx_lens);
+    if (Wg > 1) {
+        const dim3 mgrid((unsigned)((Wg - 1) * VH));
+        if (D == 64) hipLaunchKernelGGL(isd_attention_merge_kernel<64>, mgrid, dim3(256), 0, st, p, Wg, p.Mpad, ctx_lens);
+        else hipLaunchKernelGGL(isd_attention_merge_kernel<128>, mgrid, dim3(256), 0, st, p, Wg, p.Mpad, ctx_lens);
+    }
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[2]), st);
     return launch_status();
 }

@@ -56,7 +56,8 @@ def test_workspace_sizes_are_host_only_and_monotone():
     assert w > 0
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 2) == w   # operand-order K pages: same kernels
     assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 128, 16, 512, 0) == 0   # fp32 path needs none
-    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 0    # bf16 D=64: the plain path needs none
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 1) == 2 * 256 * 4 * 4 * (4 * 64 * 8 + 16 * 16)   # D = 64: half-size rows
+    assert idlm.idlm_isd_attention_workspace(256, 16, 32, 8, 64, 16, 512, 2) == 0    # operand-order K pages exist for D = 128 only
     assert idlm.idlm_isd_attention_workspace(256, 33, 32, 8, 128, 16, 512, 1) == 0
     # sized by the grid that will be launched: two slots of 64 rows (17 KB) per wavefront
     assert w == 2 * 256 * 4 * 4 * (4 * 64 * 16 + 16 * 16)

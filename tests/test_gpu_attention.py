@@ -156,11 +156,20 @@ def test_token_major_pool_and_explicit_scale():
     _check(inp, scale=0.2)
 
 
-@pytest.mark.parametrize("S,Hq,Hkv,ctx", [(1, 8, 2, [5, 70]), (4, 4, 4, [16, 33, 4]), (7, 6, 2, [100])])
+@pytest.mark.parametrize("S,Hq,Hkv,ctx", [(1, 8, 2, [5, 70]), (4, 4, 4, [16, 33, 4]), (7, 6, 2, [100]), (8, 32, 8, [300, 17, 1025]),
+                                          (16, 16, 2, [64, 700]), (32, 64, 8, [96, 450])])
 def test_bf16_head_dimension_64(S, Hq, Hkv, ctx):
-    """bf16 with D = 64 runs on the plain kernel (fp32 arithmetic over exactly widened inputs, one
-    rounding of the output)."""
-    inp = _manual(len(ctx), S, Hq, Hkv, [c + S for c in ctx], D=64, seed=S)
+    """bf16 with D = 64 runs on the same matrix-unit kernels as D = 128 (two contraction steps for the scores,
+    four sixteen-row blocks of the output): every row tiling, whole and cut sequences, both pool layouts."""
+    for token_major in (False, True):
+        inp = _manual(len(ctx), S, Hq, Hkv, [c + S for c in ctx], D=64, seed=S, token_major=token_major)
+        for nwg in (0, 1, 5, 64):
+            _check(inp, num_workgroups=nwg)
+
+
+def test_bf16_head_dimension_64_at_the_8b_shape():
+    """The 8B-class step's shape with 64-wide heads (B=64, S=8, 32 / 8 heads, contexts 1024..4096), default grid."""
+    inp = make_attention_inputs(get_config("8b", D=64), device=DEV, poison_unused=True)
     _check(inp)
 
 
@@ -206,6 +215,7 @@ def test_random_shapes_grids_and_layouts(case):
     ctx = [int(c) for c in rng.integers(S, S + hi, size=B)]
     for k in range(min(3, B)):                       # a few lengths right at tile / page edges
         ctx[k] = max(S, int(rng.choice([16, 17, 31, 32, 33, 63, 64, 65, 96, 128, 129])))
-    inp = _manual(B, S, Hkv * G, Hkv, ctx, seed=5000 + case, token_major=bool(rng.integers(0, 2)))
+    inp = _manual(B, S, Hkv * G, Hkv, ctx, seed=5000 + case, token_major=bool(rng.integers(0, 2)),
+                  D=128 if case % 3 else 64)
     for nwg in (0, int(rng.choice([1, 2, 3, 7, 17, 64, 300, 1024]))):
         _check(inp, num_workgroups=nwg)
