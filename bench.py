@@ -11,7 +11,7 @@ workload on this machine's host cores, and a `configs` block with the per-kernel
 other workloads (small, 8b, the long-context stride sweep).
 
   python bench.py                                  the default line (everything)
-  python bench.py --sections step                  only the timed step and its kernels (profiling runs)
+  python bench.py --sections step,probe            only the timed step, its kernels and the streaming probes (profiling runs)
   python bench.py --workload long32k --stride 16 --sections step
 """
 from __future__ import annotations
@@ -265,6 +265,32 @@ def cpu_baseline(att, acc, cfg, n_seq, threads=0):
     }
 
 
+def stream_probe(idlm, dev):
+    """Plain streaming kernels of known size: practical bandwidth ceiling of this device, and the reference
+    that hardware byte counters are scaled by in the committed profiles (4 GiB, so that the 256 MB memory-
+    side cache holds a negligible part of it from one pass to the next)."""
+    import torch
+    probe = torch.empty(1 << 32, dtype=torch.uint8, device=dev)
+    probe_dst = torch.empty_like(probe)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def timed(fn, n=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) / n
+
+    t_read = timed(lambda: idlm.idlm_stream_read(probe, sink))
+    t_copy = timed(lambda: idlm.idlm_stream_copy(probe, probe_dst))
+    return {"read_GBps": probe.numel() / t_read / 1e6, "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6,
+            "bytes": probe.numel()}
+
+
 def extras(case, args, hev, stream, dev, ms_per_step):
     """Everything around the step that is reported but not part of `value`."""
     import torch
@@ -284,18 +310,6 @@ def extras(case, args, hev, stream, dev, ms_per_step):
         b_.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b_) / n
-
-    # plain streaming kernels of known size: practical bandwidth ceiling of this device, and the
-    # reference that hardware byte counters are scaled by in the committed profiles (4 GiB, so that
-    # the 256 MB memory-side cache holds a negligible part of it from one pass to the next)
-    probe = torch.empty(1 << 32, dtype=torch.uint8, device=dev)
-    probe_dst = torch.empty_like(probe)
-    sink = torch.zeros(1, dtype=torch.int32, device=dev)
-    t_read = timed(lambda: idlm.idlm_stream_read(probe, sink))
-    t_copy = timed(lambda: idlm.idlm_stream_copy(probe, probe_dst))
-    res["stream_ceiling"] = {"read_GBps": probe.numel() / t_read / 1e6,
-                             "copy_read_plus_write_GBps": 2 * probe.numel() / t_copy / 1e6, "bytes": probe.numel()}
-    del probe, probe_dst
 
     # the same step launched without the timing hooks, and replayed from a captured HIP graph (the
     # calls allocate nothing and never synchronise, so they can be captured as they are)
@@ -468,14 +482,14 @@ def main():
     ap.add_argument("--k-operand-order", type=int, default=1,
                     help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
     ap.add_argument("--sections", default="all",
-                    help="comma list of step,cpu,extras,configs (all = every one; configs only with the default workload)")
+                    help="comma list of step,probe,cpu,extras,configs (all = every one; configs only with the default workload)")
     ap.add_argument("--copies", type=int, default=0, help="input copies the launches rotate over (0 = as many as the "
                                                           "memory-side cache needs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
                  % args.gpus)
-    sections = {"step", "cpu", "extras", "configs"} if args.sections == "all" else set(args.sections.split(","))
+    sections = {"step", "probe", "cpu", "extras", "configs"} if args.sections == "all" else set(args.sections.split(","))
 
     import torch
     if not torch.cuda.is_available():
@@ -588,10 +602,12 @@ def main():
         "acceptance": acceptance,
         "hbm_frac_both": {"attention": kernels[att_name]["frac_hbm"], "accept": kernels["isd_row_stats_kernel"]["frac_hbm"]},
     }
-    if "extras" in sections:
-        line.update(extras(case, args, hev, stream, dev, ms_per_step))
+    if "probe" in sections:
+        line["stream_ceiling"] = stream_probe(idlm, dev)
         for name in (att_name, "isd_row_stats_kernel"):
             kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / line["stream_ceiling"]["read_GBps"]
+    if "extras" in sections:
+        line.update(extras(case, args, hev, stream, dev, ms_per_step))
     if "cpu" in sections and args.cpu_sample > 0:
         line["cpu_baseline"] = cpu_baseline(case.att, case.acc, cfg, min(args.cpu_sample, B), args.cpu_threads)
     if "configs" in sections and args.workload == "serve256" and not args.stride and not args.head_dim:
