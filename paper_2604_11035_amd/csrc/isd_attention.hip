@@ -75,6 +75,15 @@ struct TilePlan {     // static LDS of both kernels
     int wave_sum[4];  // weight counted by each of the block's four wavefronts
 };
 
+// x of the lane whose number differs in bit 0 (XOR_LANE = 1) or bit 1 (XOR_LANE = 2): a permutation inside each quad
+// of lanes, done by the vector ALU's data-parallel-primitive path in one instruction instead of a round trip through LDS.
+template <int XOR_LANE>
+__device__ __forceinline__ uint32_t quad_xor(uint32_t x)
+{
+    constexpr int ctrl = XOR_LANE == 1 ? 0xB1 : 0x4E;   // quad_perm [1,0,3,2] / [2,3,0,1]
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, 0xF, 0xF, false);
+}
+
 // The value of x, hidden from the optimiser: what is computed from it is computed here and now
 // instead of once, ahead of the loops, and then kept in (or spilled from) a register.
 __device__ __forceinline__ int opaque(int x)
@@ -574,7 +583,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
 #pragma unroll
                                 for (int k = 0; k < E / 2; ++k) send[k] = hi ? c[lo_i][k] : c[hi_i][k];
 #pragma unroll
-                                for (int k = 0; k < E / 2; ++k) recv[k] = __shfl_xor(send[k], stage);
+                                for (int k = 0; k < E / 2; ++k) recv[k] = stage == 1 ? quad_xor<1>(send[k]) : quad_xor<2>(send[k]);
 #pragma unroll
                                 for (int k = 0; k < E / 2; ++k) {
                                     if (hi) c[lo_i][k] = recv[k]; else c[hi_i][k] = recv[k];
