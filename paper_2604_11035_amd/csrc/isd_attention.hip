@@ -84,6 +84,22 @@ __device__ __forceinline__ uint32_t quad_xor(uint32_t x)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, 0xF, 0xF, false);
 }
 
+// One 32-bit value into / out of an accumulation register.  In this file the matrix instructions keep their results
+// in ordinary vector registers, so the accumulation registers are free storage: the finished output rows of up to
+// two whole sequences wait there until the wavefront has no K/V left to read.
+__device__ __forceinline__ uint32_t acc_park(uint32_t v)
+{
+    uint32_t a;
+    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a) : "v"(v));
+    return a;
+}
+__device__ __forceinline__ uint32_t acc_fetch(uint32_t a)
+{
+    uint32_t v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
 // The value of x, hidden from the optimiser: what is computed from it is computed here and now
 // instead of once, ahead of the loops, and then kept in (or spilled from) a register.
 __device__ __forceinline__ int opaque(int x)
@@ -365,6 +381,38 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         store_q();
 
         int stash_slot = -1;   // slot of the partial held in LDS, if any
+        // Output rows of whole sequences, ready to be stored (bf16, transposed for full-row stores), parked in accumulation
+        // registers: stores that arrive in the middle of the K/V read stream cost many times their share of the bytes, so
+        // the first whole sequences of a slice (two; one where 64 rows of 128 values leave no more registers) are written
+        // only when the slice has been read.  [nb][j][dword of the chunk]
+        constexpr int kParkWords = NB * 4 * (E / 2);
+        constexpr int kParkSlots = (NB == 4 && D == 128) ? 1 : 2;
+        uint32_t park0[kParkWords], park1[kParkWords];
+        int park_b0 = 0, park_b1 = 0, nparked = 0;
+        // stores the rows of 16-row block nb of sequence bb: c[j] is chunk 4g + n%4 of rows 4*(n/4) + j
+        auto store_rows = [&](int bb, int nb, const chunk_t (&c)[4]) {
+            const int row0 = opaque(rowbase + 16 * nb + (n & 12));
+            int ip = row0 / G, gq = row0 - ip * G;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (row0 + j < M) {
+                    uint16_t* op = p.out + ((size_t)(bb * S + ip) * p.Hq + kvh * G + gq) * D + (4 * g + (n & 3)) * E;
+                    __builtin_nontemporal_store(c[j], reinterpret_cast<chunk_t*>(op));
+                }
+                if (++gq == G) { gq = 0; ++ip; }
+            }
+        };
+        auto flush_parked = [&](const uint32_t (&park)[kParkWords], int bb) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                chunk_t c[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int k = 0; k < E / 2; ++k) c[j][k] = acc_fetch(park[(nb * 4 + j) * (E / 2) + k]);
+                store_rows(bb, nb, c);
+            }
+        };
         for (int i = 0; i < remaining;) {
             // ---- a sequence starts (or continues from an earlier slice); its Q is in this wavefront's
             //      LDS already, the accumulators restart ----
@@ -590,15 +638,18 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                                 }
                             }
                         }
-                        const int row0 = opaque(rowbase + 16 * nb + (n & 12));
-                        int ip = row0 / G, gq = row0 - ip * G;
+                        if (nparked == 0) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            if (row0 + j < M) {
-                                uint16_t* op = p.out + ((size_t)(b * S + ip) * p.Hq + kvh * G + gq) * D + (4 * g + q4) * E;
-                                __builtin_nontemporal_store(c[j], reinterpret_cast<chunk_t*>(op));
-                            }
-                            if (++gq == G) { gq = 0; ++ip; }
+                            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                for (int k = 0; k < E / 2; ++k) park0[(nb * 4 + j) * (E / 2) + k] = acc_park(c[j][k]);
+                        } else if (kParkSlots > 1 && nparked == 1) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                                for (int k = 0; k < E / 2; ++k) park1[(nb * 4 + j) * (E / 2) + k] = acc_park(c[j][k]);
+                        } else {
+                            store_rows(b, nb, c);   // no room left: written at once
                         }
                     } else {
                         // partial: each row scaled to a largest magnitude of 1 and kept as fp16, [nb][j][lane]
@@ -627,10 +678,17 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                     }
                 }
                 if (!complete) stash_slot = (int)wslot;
+                if (complete && nparked < kParkSlots) {
+                    if (nparked == 0) park_b0 = b; else park_b1 = b;
+                    ++nparked;
+                }
             }
             store_q();
             b = pb; kt = pkt; nt = pnt;   // first tile of the next sequence (unused after the last one)
         }
+        // the slice has been read: everything that waited is written now
+        if (nparked > 0) flush_parked(park0, park_b0);
+        if (kParkSlots > 1 && nparked > 1) flush_parked(park1, park_b1);
         if (stash_slot >= 0) flush_stash(stash_slot);
     }
 }
