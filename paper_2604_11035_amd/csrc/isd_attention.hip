@@ -549,6 +549,159 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 }
             };
 
+
+            if constexpr (NB == 4) {
+                // ---- 64 rows per wavefront (NB = 4): one tile with the two halves of its rows interleaved ----
+                // A wavefront of 64 rows is alone on its SIMD, and it issues in order: while its matrix instructions run
+                // nothing else does unless the instruction stream itself puts vector work between them.  So the tile is
+                // written as four phases whose order of issue is pinned step by step:
+                //   1. scores of blocks 0, 1                         (matrix unit; Q operands four reads ahead)
+                //   2. scores of blocks 2, 3  +  weights of 0, 1     (matrix unit and vector ALU side by side)
+                //   3. values of blocks 0, 1  +  weights of 2, 3     (V is transposed block by block on the way)
+                //   4. values of blocks 2, 3  +  the transposes again (cheaper than keeping 32 registers of transposed V)
+                // The rescale of a late overshoot is ordinary arithmetic on the accumulators here (they are vector registers
+                // in this file) inside a branch that is practically never taken.
+                auto fix_refs = [&](int nb0) {
+    #pragma unroll
+                    for (int nb = nb0; nb < nb0 + 2; ++nb) {
+                        float rm = smax[nb] * cs;
+                        rm = fmaxf(rm, __shfl_xor(rm, 16));
+                        rm = fmaxf(rm, __shfl_xor(rm, 32));
+                        const bool fresh = mref[nb] == -INFINITY;
+                        const bool late = !fresh && rm > mref[nb] + kRescaleSlack;
+                        const float mnew = fmaxf(mref[nb], rm);
+                        const float alpha = late ? fast_exp2(mref[nb] - mnew) : 1.f;
+                        lacc[nb] *= alpha;
+    #pragma unroll
+                        for (int e = 0; e < E; ++e) oacc[e][nb] *= alpha;
+                        set_ref(nb, (fresh || late) ? mnew : mref[nb]);
+                    }
+                };
+                auto tile_interleaved = [&](int tb) {
+                    asm volatile("" ::: "memory");   // Q comes out of LDS anew for every tile instead of staying in registers
+                    constexpr int kOps = 2 * KS;     // Q operands of one half of the rows
+                    constexpr int kAhead = kOps < 4 ? kOps : 4;
+                    constexpr int kPer = 16 / kOps;  // weights of the other half computed per step of phase 2
+                    constexpr int kPerE = 16 / E;    // ... per step of phase 3
+                    const bool masked = tb + 32 > ctx - S + 1;
+                    auto mask_half = [&](int nb0) {
+    #pragma unroll
+                        for (int nb = nb0; nb < nb0 + 2; ++nb) {
+                            const int lim = ctx - S + qpos[nb];   // last key this row may see
+    #pragma unroll
+                            for (int tblk = 0; tblk < 2; ++tblk)
+    #pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (tb + 16 * tblk + 4 * g + j > lim) sacc[nb][tblk][j] = -INFINITY;
+                        }
+                    };
+                    auto half_max = [&](int nb0) {
+                        bool overshoot = false;
+    #pragma unroll
+                        for (int nb = nb0; nb < nb0 + 2; ++nb) {
+                            float mx = fmaxf(fmaxf(sacc[nb][0][0], sacc[nb][0][1]), sacc[nb][0][2]);
+                            mx = fmaxf(fmaxf(mx, sacc[nb][0][3]), sacc[nb][1][0]);
+                            mx = fmaxf(fmaxf(mx, sacc[nb][1][1]), sacc[nb][1][2]);
+                            smax[nb] = fmaxf(mx, sacc[nb][1][3]);
+                            overshoot |= smax[nb] > over[nb];
+                        }
+                        return __any(overshoot) != 0;
+                    };
+                    // weight number w (0 .. 15) of the half that starts at block nb0: block nb0 + w/8, entry w%8
+                    float pw[16];
+                    auto weight = [&](int nb0, int w) {
+                        const int nb = nb0 + (w >> 3), tblk = (w >> 2) & 1, j = w & 3;
+                        pw[w] = fast_exp2(fmaf(sacc[nb][tblk][j], cs, nref[nb]));
+                    };
+                    bf16x8 pt[NB];
+                    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
+                    auto pack_half = [&](int nb0) {
+    #pragma unroll
+                        for (int w = 0; w < 16; ++w) pt[nb0 + (w >> 3)][w & 7] = (__bf16)pw[w];
+                        lacc[nb0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pt[nb0], lacc[nb0], 0, 0, 0);
+                        lacc[nb0 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pt[nb0 + 1], lacc[nb0 + 1], 0, 0, 0);
+                    };
+                    auto transposed_v = [&](int e) {
+                        u32x4 vt;
+    #pragma unroll
+                        for (int wp = 0; wp < 4; ++wp) {
+                            const uint32_t x = tv[2 * wp][e >> 1], y = tv[2 * wp + 1][e >> 1];
+                            vt[wp] = (e & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+                        }
+                        return __builtin_bit_cast(bf16x8, vt);
+                    };
+    #pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        sacc[nb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        sacc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    // ---- phase 1 ----
+                    bf16x8 qb[2 * kOps];
+    #pragma unroll
+                    for (int r = 0; r < kAhead; ++r) qb[r] = __builtin_bit_cast(bf16x8, qlds[r * 64]);
+                    __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                    for (int r = 0; r < kOps; ++r) {
+                        const int nb = r / KS, ks = r % KS;
+                        sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][ks], qb[r], sacc[nb][0], 0, 0, 0);
+                        sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][ks], qb[r], sacc[nb][1], 0, 0, 0);
+                        qb[r + kAhead] = __builtin_bit_cast(bf16x8, qlds[(r + kAhead) * 64]);   // runs on into the second half
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (masked) mask_half(0);
+                    if (half_max(0)) fix_refs(0);
+                    // ---- phase 2 ----
+    #pragma unroll
+                    for (int r = 0; r < kOps; ++r) {
+                        const int nb = 2 + r / KS, ks = r % KS;
+                        sacc[nb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[0][ks], qb[kOps + r], sacc[nb][0], 0, 0, 0);
+                        sacc[nb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tk[1][ks], qb[kOps + r], sacc[nb][1], 0, 0, 0);
+                        if (r + kAhead < kOps) qb[kOps + r + kAhead] = __builtin_bit_cast(bf16x8, qlds[(kOps + r + kAhead) * 64]);
+    #pragma unroll
+                        for (int u = 0; u < kPer; ++u) weight(0, r * kPer + u);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    load_k(npg0, npg1);   // K registers are free again: next tile's K goes in flight
+                    pack_half(0);
+                    if (masked) {
+                        mask_half(2);
+                        // value rows beyond the context may hold anything (NaN included): zero them
+    #pragma unroll
+                        for (int jj = 0; jj < 8; ++jj)
+                            if (tb + 16 * (jj >> 2) + 4 * g + (jj & 3) >= ctx) tv[jj] = chunk_t(0u);
+                    }
+                    if (half_max(2)) fix_refs(2);
+                    // ---- phase 3 ----
+                    __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const bf16x8 va = transposed_v(e);
+                        oacc[e][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[0], oacc[e][0], 0, 0, 0);
+                        oacc[e][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[1], oacc[e][1], 0, 0, 0);
+    #pragma unroll
+                        for (int u = 0; u < kPerE; ++u) weight(2, e * kPerE + u);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    pack_half(2);
+                    // ---- phase 4 ----
+    #pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const bf16x8 va = transposed_v(e);
+                        oacc[e][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[2], oacc[e][2], 0, 0, 0);
+                        oacc[e][3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pt[3], oacc[e][3], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    load_v(npg0, npg1);   // V registers are free again
+                    // ---- cursors: c1 becomes the tile in flight's successor (scalar work only) ----
+                    pb = c1b; pkt = c1kt; pnt = c1nt;
+                    if (i + 2 < remaining) {
+                        advance(c1b, c1kt, c1nt);
+                        page_ids(c1b, c1kt, npg0, npg1);
+                    }
+                };
+
+                for (int t = 0; t < n_in; ++t, ++i) tile_interleaved(32 * (kt + t));
+            } else
             for (int t = 0; t < n_in;) {
                 bool rescale = false;
                 for (; t < n_in; ++t, ++i) {
