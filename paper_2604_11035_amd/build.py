@@ -12,7 +12,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libidlm_isd.so"
-SOURCES = ["isd_attention.hip", "isd_accept.hip", "isd_accept_general.hip", "isd_accept_filtered.hip", "isd_loop.hip", "isd_lora.hip", "idlm_misc.hip"]
+SOURCES = ["isd_attention.hip", "isd_attention_shared.hip", "isd_accept.hip", "isd_accept_general.hip", "isd_accept_filtered.hip", "isd_loop.hip", "isd_lora.hip", "idlm_misc.hip"]
 # Packed fp32 VALU forms are switched off for all device code (they have produced wrong
 # results on the target machines); the host pass does not know the feature and says so.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
@@ -21,7 +21,8 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
 # Per-file additions.  The attention kernel's score accumulators are read by vector arithmetic right after
 # the matrix instructions that produce them: with the results of matrix instructions in ordinary vector
 # registers there are no copies out of accumulation registers in its tile loop.
-FILE_FLAGS = {"isd_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+FILE_FLAGS = {"isd_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+              "isd_attention_shared.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 NOISE = "is not a recognized feature for this target"
 
 

@@ -27,183 +27,9 @@
 //
 // HBM-bound for S*G below the machine's flop/byte ridge: algorithmic traffic is one read of
 // the sequence's K and V rows (2 * Hkv * D * 2 bytes per context token).
-#include "idlm_common.h"
+#include "isd_attention_plan.h"
 
 namespace idlm {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-
-constexpr int kMaxWorkgroups = 1024;      // upper bound of a forced persistent grid
-constexpr int kDefaultWorkgroups = 256;   // upper bound of the grid the library chooses itself (one workgroup per compute unit)
-
-struct AttnParams {
-    const uint16_t* q;
-    const uint16_t* k;
-    const uint16_t* v;
-    uint16_t* out;
-    void* ws_o;     // [2*NW][NB][4][64] partial outputs of a slot (2v: first sequence of wavefront v's slice, 2v+1: its
-                    //                   last): D/16 fp16 per entry, normalised per row to a largest magnitude of 1
-    f32x4* ws_ml;   // [2*NW][NB][16]    per row: reference exponent, denominator l, largest magnitude of O / l, unused
-    int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
-    int num_pages;
-    int64_t page_stride, head_stride, token_stride;
-    float scale_log2;
-};
-
-// A rescale of the running reference exponent is skipped while no score exceeds it by more
-// than this many powers of two: probabilities then stay below 2^12, harmless in fp32 / bf16
-// (bf16 has fp32's exponent range), and after the first tile the rescale almost never runs.
-constexpr float kRescaleSlack = 12.0f;
-
-// ---- the tile list and its partition -------------------------------------------------------
-
-// The list is cut into slices of equal COST, not of equal tile count: besides its tiles every
-// sequence costs a wavefront about three tiles' worth of time (Q in, rows out; measured 8 us per
-// sequence part against 2.6 us per tile on the serving workload), so positions are counted in
-// "weights", tiles + kSeqCost per sequence.  A cut that falls into a sequence's extra weight is
-// moved to the end of that sequence.
-constexpr int kSeqCost = 3;
-
-struct TilePlan {     // static LDS of both kernels
-    int incl[256];    // inclusive prefix sums of the per-thread sequence weights
-    int wave_sum[4];  // weight counted by each of the block's four wavefronts
-};
-
-// x of the lane whose number differs in bit 0 (XOR_LANE = 1) or bit 1 (XOR_LANE = 2): a permutation inside each quad
-// of lanes, done by the vector ALU's data-parallel-primitive path in one instruction instead of a round trip through LDS.
-template <int XOR_LANE>
-__device__ __forceinline__ uint32_t quad_xor(uint32_t x)
-{
-    constexpr int ctrl = XOR_LANE == 1 ? 0xB1 : 0x4E;   // quad_perm [1,0,3,2] / [2,3,0,1]
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, 0xF, 0xF, false);
-}
-
-// One 32-bit value into / out of an accumulation register.  In this file the matrix instructions keep their results
-// in ordinary vector registers, so the accumulation registers are free storage: the finished output rows of up to
-// two whole sequences wait there until the wavefront has no K/V left to read.
-__device__ __forceinline__ uint32_t acc_park(uint32_t v)
-{
-    uint32_t a;
-    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a) : "v"(v));
-    return a;
-}
-__device__ __forceinline__ uint32_t acc_fetch(uint32_t a)
-{
-    uint32_t v;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
-    return v;
-}
-
-// The value of x, hidden from the optimiser: what is computed from it is computed here and now
-// instead of once, ahead of the loops, and then kept in (or spilled from) a register.
-__device__ __forceinline__ int opaque(int x)
-{
-    asm volatile("" : "+v"(x));
-    return x;
-}
-
-// 32-token tiles of sequence b (for one KV head).  A context longer than the block table can
-// describe is a broken precondition; the table is never walked past its end.
-__device__ __forceinline__ int seq_tiles(const AttnParams& p, const int32_t* __restrict__ ctx_lens, int b)
-{
-    const int c = min(ctx_lens[b], p.max_pages * 16);
-    return c > 0 ? (c + 31) >> 5 : 0;
-}
-
-// Block-wide inclusive scan of sequence weights (thread t sums sequences [t*per, (t+1)*per)): a
-// shuffle scan inside each wavefront, then the wavefront totals through LDS - two barriers in all.
-// Returns the total weight of one head's list (its tiles + kSeqCost * B).  Every thread of the
-// block must call it.
-__device__ __forceinline__ int plan_scan(const AttnParams& p, const int32_t* __restrict__ ctx_lens, TilePlan& plan)
-{
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int per = (p.B + 255) >> 8;
-    const int b0 = tid * per, b1 = min(p.B, b0 + per);
-    int x = 0;
-    for (int b = b0; b < b1; ++b) x += seq_tiles(p, ctx_lens, b) + kSeqCost;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(x, off);
-        if (lane >= off) x += y;
-    }
-    if (lane == 63) plan.wave_sum[w] = x;
-    __syncthreads();
-    int before = 0, total = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int sk = plan.wave_sum[k];
-        before += (k < w) ? sk : 0;
-        total += sk;
-    }
-    plan.incl[tid] = x + before;
-    __syncthreads();
-    return __builtin_amdgcn_readfirstlane(total);   // wave-uniform: keep it in a scalar register
-}
-
-// Sequence b whose weight range holds weight position y (0 <= y < total weight) and the weight
-// before it.  A wavefront-level lookup (after plan_scan): y must be the same in all lanes of the
-// calling wavefront, different wavefronts may look up different positions, nobody waits for anybody.
-__device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* __restrict__ ctx_lens, const TilePlan& plan,
-                                            int y, int& b, int& before)
-{
-    const int lane = threadIdx.x & 63;
-    int fb = 0, fpre = 0;
-    bool found = false;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int t = lane + 64 * k;
-        const int incl = plan.incl[t];
-        const int excl = t ? plan.incl[t - 1] : 0;
-        if (excl <= y && y < incl) {     // true for exactly one t of the 256
-            const int per = (p.B + 255) >> 8;
-            int bb = t * per, acc = excl;
-            for (;;) {
-                const int wgt = seq_tiles(p, ctx_lens, bb) + kSeqCost;
-                if (y < acc + wgt) break;
-                acc += wgt;
-                ++bb;
-            }
-            fb = bb;
-            fpre = acc;
-            found = true;
-        }
-    }
-    // the same value in every lane: scalar registers, so that everything derived from it
-    // (table pointer, page ids, loop bounds) stays on the scalar unit
-    const unsigned long long mask = __ballot(found);
-    const int src = __builtin_amdgcn_readfirstlane((int)__ffsll((long long)mask) - 1);
-    b = __builtin_amdgcn_readlane(fb, src);
-    before = __builtin_amdgcn_readlane(fpre, src);
-}
-
-// First tile (position in the head's tile list) of slice j of Wg, the sequence b that holds it
-// and the tiles before b.  j >= Wg gives the end of the list (b and pre are then not set).
-// Wavefront-level like plan_locate.
-__device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32_t* __restrict__ ctx_lens, const TilePlan& plan,
-                                                int total_weight, int Wg, int j, int& b, int& pre)
-{
-    const int total_tiles = total_weight - kSeqCost * p.B;
-    if (j >= Wg) return total_tiles;
-    const int y = (int)((int64_t)total_weight * j / Wg);
-    int before;
-    plan_locate(p, ctx_lens, plan, y, b, before);
-    pre = before - kSeqCost * b;
-    int nt = seq_tiles(p, ctx_lens, b);
-    const int x = pre + min(y - before, nt);
-    // a cut at the end of a sequence belongs to the next sequence that has tiles
-    while (x >= pre + nt && x < total_tiles) {
-        pre += nt;
-        ++b;
-        nt = seq_tiles(p, ctx_lens, b);
-    }
-    return x;
-}
 
 // The block table and the context lengths are separate __restrict__ kernel arguments: nothing
 // the kernel stores can alias them, so their wave-uniform loads stay on the scalar unit and do
@@ -223,10 +49,6 @@ __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32
 //
 // D is the head dimension, 64 or 128: D/32 contraction steps for St, D/16 sixteen-row blocks of Ot, and a lane's
 // share of a V row (and of an output row) is a chunk of D/16 consecutive values, 8 or 16 bytes.
-template <int D> struct LaneChunk;
-template <> struct LaneChunk<128> { typedef u32x4 type; };
-template <> struct LaneChunk<64> { typedef u32x2 type; };
-
 template <int NB, int LAYOUT, int D>
 __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParams p,
                                                                  const int32_t* __restrict__ block_table,
@@ -943,8 +765,15 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
             bf16xE ov;
 #pragma unroll
             for (int e = 0; e < E; ++e) ov[e] = (__bf16)(acc[nb][e] * inv);
-            uint16_t* op = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * D + 4 * E * g + E * j;
-            *reinterpret_cast<bf16xE*>(op) = ov;
+            uint16_t* orow = p.out + ((size_t)(b * p.S + i) * p.Hq + kvh * p.G + gq) * D;
+            if (D == 128 && p.partial_layout == 1) {
+                // entries of the shared-tile kernel: values 32 j + 4 g .. + 3 and 32 j + 16 + 4 g .. + 3
+                typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+                *reinterpret_cast<bf16x4_t*>(orow + 32 * j + 4 * g) = bf16x4_t{ov[0], ov[1], ov[2], ov[3]};
+                *reinterpret_cast<bf16x4_t*>(orow + 32 * j + 16 + 4 * g) = bf16x4_t{ov[E - 4], ov[E - 3], ov[E - 2], ov[E - 1]};
+            } else {
+                *reinterpret_cast<bf16xE*>(orow + 4 * E * g + E * j) = ov;
+            }
         }
     }
 }
@@ -1048,9 +877,15 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
     return true;
 }
 
+// More than 64 rows per KV head with 128-wide heads go to the kernel whose wavefronts share the K/V tiles through
+// LDS (its tile is built for D = 128): workgroups of four wavefronts with 32 rows each, two workgroups per compute unit
+static bool uses_shared_kernel(int M, int D) { return D == 128 && M > 64; }
+static int default_workgroups(int M, int D) { return uses_shared_kernel(M, D) ? 2 * kDefaultWorkgroups : kDefaultWorkgroups; }
+
 // 16-row blocks per wavefront (NB) and groups of 16*NB rows per KV head (RG) for M = S*G query rows
-static void row_tiling(int M, int* NB, int* RG)
+static void row_tiling(int M, int D, int* NB, int* RG)
 {
+    if (uses_shared_kernel(M, D)) { *NB = 2; *RG = M <= 128 ? 4 : 8; return; }
     if (M <= 16) { *NB = 1; *RG = 1; }
     else if (M <= 32) { *NB = 2; *RG = 1; }
     else if (M <= 64) { *NB = 4; *RG = 1; }
@@ -1089,9 +924,9 @@ using namespace idlm;
 
 // bytes of the partial-result slots of a grid of W workgroups: two slots of 16*NB rows per wavefront, each row
 // as D fp16 values plus four fp32 row scalars
-static size_t partial_slots_bytes(int NB, int W, int D)
+static size_t partial_slots_bytes(int NB, int W, int waves_per_workgroup, int D)
 {
-    const size_t slots = (size_t)2 * W * 4;
+    const size_t slots = (size_t)2 * W * waves_per_workgroup;
     return slots * NB * (4 * 64 * (size_t)(D / 8) + 16 * sizeof(f32x4));
 }
 
@@ -1104,8 +939,9 @@ extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq,
     if (num_workgroups < 0 || num_workgroups > kMaxWorkgroups) return 0;
     if (!uses_mfma_path(D, dtype) || B == 0) return 0;
     int NB, RG;
-    row_tiling(S * (Hq / Hkv), &NB, &RG);
-    return partial_slots_bytes(NB, num_workgroups ? num_workgroups : kDefaultWorkgroups, D);
+    const int M = S * (Hq / Hkv);
+    row_tiling(M, D, &NB, &RG);
+    return partial_slots_bytes(NB, num_workgroups ? num_workgroups : default_workgroups(M, D), 4, D);
 }
 
 extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const void* v_cache,
@@ -1157,6 +993,8 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     if (!aligned(workspace, 256)) return IDLM_ERR_ALIGN;
 
     // one persistent workgroup per compute unit (a workgroup holds a whole CU's registers)
+    const bool shared = uses_shared_kernel(S * G, D);
+    const int wpw = 4;   // wavefronts per workgroup
     int W = num_workgroups;
     if (W == 0) {
         int dev = 0, cus = 0;
@@ -1164,19 +1002,20 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             return IDLM_ERR_LAUNCH;
         W = cus > kDefaultWorkgroups ? kDefaultWorkgroups : cus;
+        if (shared) W *= 2;
         // A batch that cannot hold more than a few tiles per wavefront gets a smaller grid: slices
         // shorter than about 16 tiles only multiply the partial results that have to be joined.  The
         // bound uses what the host knows (B and the width of the block table).
         int nb_, rg_;
-        row_tiling(S * G, &nb_, &rg_);
+        row_tiling(S * G, D, &nb_, &rg_);
         const int64_t max_tiles = (int64_t)B * ((max_pages_per_seq + 1) / 2);
         const int64_t wavefronts = (max_tiles / 16 > 0 ? max_tiles / 16 : 1) * Hkv * rg_;
-        if ((wavefronts + 3) / 4 < W) W = (int)((wavefronts + 3) / 4);
+        if ((wavefronts + wpw - 1) / wpw < W) W = (int)((wavefronts + wpw - 1) / wpw);
     }
 
     // the slots of the grid that is launched fit: it is never larger than the one the workspace was sized for
     int NB, RG_;
-    row_tiling(S * G, &NB, &RG_);
+    row_tiling(S * G, D, &NB, &RG_);
 
     AttnParams p;
     p.q = static_cast<const uint16_t*>(q);
@@ -1187,7 +1026,8 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.num_pages = num_pages;
     p.RG = RG_;
     p.Mpad = 16 * NB;
-    const size_t slots = (size_t)2 * W * 4;
+    p.partial_layout = shared ? 1 : 0;
+    const size_t slots = (size_t)2 * W * wpw;
     p.ws_o = workspace;
     p.ws_ml = reinterpret_cast<f32x4*>(static_cast<char*>(workspace) + slots * NB * 4 * 64 * (size_t)(D / 8));
     p.page_stride = page_stride; p.head_stride = head_stride; p.token_stride = token_stride;
@@ -1198,14 +1038,15 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     // per wavefront: Q operands of its current sequence, one parked partial result, that partial's row scalars
     const size_t shmem = (size_t)4 * NB * ((D / 32) * 64 * 16 + 4 * 64 * (D / 8) + 16 * 16);
     const int layout = dtype == IDLM_DTYPE_BF16_KOP ? 2 : (token_stride == D ? 1 : 0);
-    const int rc = D == 64 ? (layout == 1 ? launch_main<1, 64>(NB, W, shmem, st, p, block_table, ctx_lens)
+    const int rc = shared ? launch_shared_kernel(layout, W, st, p, block_table, ctx_lens)
+                 : D == 64 ? (layout == 1 ? launch_main<1, 64>(NB, W, shmem, st, p, block_table, ctx_lens)
                                           : launch_main<0, 64>(NB, W, shmem, st, p, block_table, ctx_lens))
                  : layout == 2 ? launch_main<2, 128>(NB, W, shmem, st, p, block_table, ctx_lens)
                  : layout == 1 ? launch_main<1, 128>(NB, W, shmem, st, p, block_table, ctx_lens)
                                : launch_main<0, 128>(NB, W, shmem, st, p, block_table, ctx_lens);
     if (rc != IDLM_OK) return rc;
     if (events) (void)hipEventRecord(static_cast<hipEvent_t>(events[1]), st);
-    const int VH = Hkv * p.RG, NW = W * 4;
+    const int VH = Hkv * p.RG, NW = W * wpw;
     const int Wg = NW >= VH ? NW / VH : 1;   // slices per virtual head, as in the main kernel
     if (Wg > 1) {
         const dim3 mgrid((unsigned)((Wg - 1) * VH));
