@@ -102,16 +102,20 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
     const lds_bytes ring = (lds_bytes)smem;
     const uint32_t ring_addr = (uint32_t)(size_t)ring;
 
-    // ---- what this wavefront requests of every tile: four blocks of 1 KB, two per 16-token page ----
-    // K blocks (page 0 / 1, contraction step w) in A-operand order (lane (n, g): token n, values 32 w + 8 g .. + 7).
-    // V blocks w and w + 4: rows (tokens) 4 w .. 4 w + 3 of either page, 256 bytes each; lane l brings 16-byte chunk
-    // (l % 16) ^ 2 (t % 8) of row t = 4 w + l / 16 to place l % 16 of that row.  The exclusive-or spreads the rows over
-    // the LDS banks for the transposing reads below, which take 32 bytes of sixteen different rows at a time.
+    // ---- what this wavefront requests of every tile: four blocks of 1 KB, all of 16-token page w / 2 (one page id and
+    //      one pair of page addresses per wavefront and tile) ----
+    // K blocks: contraction steps 2 (w % 2) and 2 (w % 2) + 1 in A-operand order (lane (n, g): token n, values
+    // 32 step + 8 g .. + 7).
+    // V blocks: rows (tokens of the page) 8 (w % 2) .. + 3 and 8 (w % 2) + 4 .. + 7, 256 bytes each; lane l brings 16-byte
+    // chunk (l % 16) ^ 2 (t % 8) of row t = first row + l / 16 to place l % 16 of that row.  The exclusive-or spreads the
+    // rows over the LDS banks for the transposing reads below, which take 32 bytes of sixteen different rows at a time.
     const int tstride = LAYOUT == 0 ? (int)p.token_stride : D;
-    const uint32_t koff = LAYOUT == 2 ? (uint32_t)(lane * 16 + 1024 * w) : (uint32_t)(2 * (n * tstride + g * 8) + 64 * w);
-    const int vrow = 4 * w + g;                             // token inside the 16-token page
-    const int vchunk = n ^ (2 * ((4 * (w & 1) + g) & 7));   // t % 8 = 4 (w % 2) + g
-    const uint32_t voff = (uint32_t)(2 * (vrow * tstride + 8 * vchunk));
+    const int pw = w >> 1, hw = w & 1;
+    const uint32_t koff_a = LAYOUT == 2 ? (uint32_t)(lane * 16 + 1024 * (2 * hw)) : (uint32_t)(2 * (n * tstride + g * 8) + 64 * (2 * hw));
+    const uint32_t koff_b = koff_a + (LAYOUT == 2 ? 1024u : 64u);
+    const uint32_t voff_a = (uint32_t)(2 * ((8 * hw + g) * tstride + 8 * (n ^ (2 * g))));
+    const uint32_t voff_b = (uint32_t)(2 * ((8 * hw + 4 + g) * tstride + 8 * (n ^ (2 * (4 + g)))));
+    const uint32_t kdst = (uint32_t)((4 * pw + 2 * hw) * 1024), vdst = (uint32_t)(kTileBytes / 2 + (4 * pw + 2 * hw) * 1024);
 
     // ---- what this lane reads of every tile ----
     // K operand (page tblk, step ks): 16 bytes at (4 tblk + ks) * 1024 + 16 * lane.
@@ -135,24 +139,18 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
         const uint64_t vhp = reinterpret_cast<uint64_t>(p.v + kvh * p.head_stride);
 
         auto seq_pages = [&](int b) { return (min(ctx_lens[b], p.max_pages * 16) + 15) >> 4; };
-        // Page ids of tile kt of sequence b: page_words issues the reads of the table, page_clamp is their first use
-        // (a pair of tiles later).  The second id is only read when that page belongs to the sequence (np = its number
-        // of pages); otherwise the first page is read again and masked out.
-        auto page_words = [&](int b, int kt, int np, int& pg0, int& pg1) {
+        // Id of this wavefront's page of tile kt of sequence b: page_word issues the read of the table, the request one
+        // tile later is its first use.  The tile's second page is only read when it belongs to the sequence (np = its
+        // number of pages); otherwise the first page is read again and masked out.
+        auto page_word = [&](int b, int kt, int np) {
             const int32_t* __restrict__ tab = block_table + (size_t)b * p.max_pages;
-            pg0 = tab[2 * kt];
-            pg1 = tab[(2 * kt + 1 < np) ? 2 * kt + 1 : 2 * kt];
-        };
-        // a page id outside the pool breaks the caller's side of the contract; the read stays inside the pool anyway
-        auto page_clamp = [&](int& pg0, int& pg1) {
-            pg0 = min(max(pg0, 0), p.num_pages - 1);
-            pg1 = min(max(pg1, 0), p.num_pages - 1);
+            return tab[(pw && 2 * kt + 1 < np) ? 2 * kt + 1 : 2 * kt];
         };
 
         // ---- the request cursor: the next tile to be requested, the page ids of that tile and of its successor,
         //      the number of tiles requested so far ----
         int db = b0, dnt = seq_tiles(p, ctx_lens, db), dkt = slice_begin - pre0, dnp = seq_pages(db);
-        int id0, id1, issued = 0, cpos = 0;
+        int id, issued = 0, cpos = 0;
         auto cursor_step = [&]() {   // the cursor stays on the last tile of the slice
             if (cpos + 1 < remaining) {
                 ++cpos;
@@ -167,18 +165,19 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
         // Past the end of the slice the last tile is requested again (nobody reads it): the number of outstanding
         // requests is then the same for every tile, which is what dma_wait counts on.
         auto request_tile = [&]() {
-            page_clamp(id0, id1);
-            const uint32_t dst = ring_addr + (uint32_t)((issued & (kRing - 1)) * kTileBytes + w * 1024);
-            const uint64_t pb0 = 2 * (uint64_t)id0 * (uint64_t)p.page_stride, pb1 = 2 * (uint64_t)id1 * (uint64_t)p.page_stride;
-            dma16(kh + pb0, koff, dst);
-            dma16(kh + pb1, koff, dst + 4096);
-            dma16(vhp + pb0, voff, dst + kTileBytes / 2);
-            dma16(vhp + pb1, voff, dst + kTileBytes / 2 + 4096);
+            // a page id outside the pool breaks the caller's side of the contract; the read stays inside the pool anyway
+            const int pg = min(max(id, 0), p.num_pages - 1);
+            const uint32_t dst = ring_addr + (uint32_t)((issued & (kRing - 1)) * kTileBytes);
+            const uint64_t pb = 2 * (uint64_t)pg * (uint64_t)p.page_stride;
+            dma16(kh + pb, koff_a, dst + kdst);
+            dma16(kh + pb, koff_b, dst + kdst + 1024);
+            dma16(vhp + pb, voff_a, dst + vdst);
+            dma16(vhp + pb, voff_b, dst + vdst + 1024);
             ++issued;
             cursor_step();
         };
-        // the reads of the cursor's page ids
-        auto next_ids = [&]() { page_words(db, dkt, dnp, id0, id1); };
+        // the read of the cursor's page id
+        auto next_ids = [&]() { id = page_word(db, dkt, dnp); };
         static_assert((kRing & (kRing - 1)) == 0, "ring slots are taken modulo a power of two");
         next_ids();
 #pragma unroll
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
 
             // one tile from ring slot `slot`
             auto tile = [&](int tb, int slot) {
-                const uint32_t vl = (uint32_t)(slot * kTileBytes + kTileBytes / 2) + vread0;   // offset in the ring
+                const lds_bytes vl = ring + (slot * kTileBytes + kTileBytes / 2);
                 u32x4 vt[E];
                 __builtin_amdgcn_sched_barrier(0);
                 // ---- St = K Qt ----
@@ -277,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
                 request_tile();
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
-                    const lds_bytes ve = ring + (vl ^ (uint32_t)(32 * e));
+                    const lds_bytes ve = vl + (vread0 ^ (uint32_t)(32 * e));
                     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)ve);
                     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(ve + 4096));
                     vt[e] = __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
