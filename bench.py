@@ -157,6 +157,14 @@ def stats_of(samples):
     return {"ms": sum(v) / len(v), "min_ms": v[0], "median_ms": v[len(v) // 2], "max_ms": v[-1], "samples": len(v)}
 
 
+def attention_kernel_name(cfg):
+    """The kernel idlm_isd_attention launches for this configuration (bf16: more than 64 query rows per KV head with
+    128-wide heads go to the kernel that shares the K/V tiles of a workgroup through LDS)."""
+    if cfg.dtype != "bf16":
+        return "isd_attention_f32_kernel"
+    return "isd_attention_shared_kernel" if cfg.D == 128 and cfg.S * (cfg.Hq // cfg.Hkv) > 64 else "isd_attention_bf16_kernel"
+
+
 def kernel_record(case, hev, events):
     """Per-kernel figures from the hooked launches: events = [(attention events, accept events), ...]."""
     cfg = case.cfg
@@ -166,9 +174,8 @@ def kernel_record(case, hev, events):
     att_flops = attention_flops(case.ctx_np, cfg)
     acc_bytes = cfg.B * cfg.S * cfg.V * 4
     a, r = t["attention"], t["row_stats"]
-    mfma = cfg.dtype == "bf16" and cfg.D == 128
     kernels = {
-        ("isd_attention_bf16_kernel" if mfma else "isd_attention_f32_kernel"): dict(
+        attention_kernel_name(cfg): dict(
             a, algorithmic_bytes=att_bytes, GBps=att_bytes / a["ms"] / 1e6, frac_hbm=att_bytes / a["ms"] / 1e6 / HBM_PEAK_GBS,
             TFLOPs=att_flops / a["ms"] / 1e9, frac_mfma=att_flops / a["ms"] / 1e9 / MFMA_BF16_PEAK_TFLOPS),
         "isd_attention_merge_kernel": {"ms": t["merge"]["ms"]},
@@ -510,7 +517,8 @@ def main():
     case = probe if ncopies == 1 else Case(cfg, dev, copies=ncopies, kop=args.k_operand_order, workgroups=args.workgroups)
     del probe
     B, S, V = cfg.B, cfg.S, cfg.V
-    nwg = args.workgroups or torch.cuda.get_device_properties(0).multi_processor_count
+    nwg = args.workgroups or torch.cuda.get_device_properties(0).multi_processor_count * (
+        2 if attention_kernel_name(cfg) == "isd_attention_shared_kernel" else 1)   # the library's own choice
 
     for i in range(args.warmup):
         case.step(i, stream)

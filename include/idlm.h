@@ -36,7 +36,7 @@
 extern "C" {
 #endif
 
-#define IDLM_VERSION 200 /* major*10000 + minor*100 + patch */
+#define IDLM_VERSION 201 /* major*10000 + minor*100 + patch */
 
 enum {
     IDLM_OK = 0,
@@ -97,8 +97,9 @@ enum {
  *             (plain path, one wavefront per (row, head) with fp32 arithmetic, for correctness
  *             rather than speed).
  * num_workgroups  size of the persistent grid that shares the batch's 32-token tiles evenly;
- *             0 = one workgroup per compute unit of the current device (at most 256), fewer when B and the
- *             width of the block table bound the work to a few tiles per wavefront (the setting to use);
+ *             0 = one workgroup per compute unit of the current device (at most 256; two per compute unit, at
+ *             most 512, when D = 128 and more than 64 query rows share a KV head, S*G > 64), fewer when B and
+ *             the width of the block table bound the work to a few tiles per wavefront (the setting to use);
  *             1..1024 forces a grid (testing, or leaving compute units to other streams).
  * workspace   at least idlm_isd_attention_workspace(..., num_workgroups) bytes, 256-byte aligned (MFMA path:
  *             partial results of the sequences that a slice boundary cuts;
@@ -114,9 +115,9 @@ int idlm_isd_attention(const void* q, const void* k_cache, const void* v_cache,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace idlm_isd_attention needs for these shapes and this num_workgroups (the value
- * that will be passed to the call; 0 = the library's own choice, at most 256 workgroups): two
- * partial-result slots per wavefront of the grid, 35 MB for the default grid at D = 128 and
- * S*G >= 33 query rows per KV head.  Host-only, no GPU needed.  Returns 0 for shapes that are rejected anyway. */
+ * that will be passed to the call; 0 = the library's own choice, at most 256 workgroups, or 512 of half the rows
+ * each for D = 128 and S*G > 64): two partial-result slots per wavefront of the grid, 35 MB for the default grid
+ * at D = 128 and S*G >= 33 query rows per KV head.  Host-only, no GPU needed.  Returns 0 for shapes that are rejected anyway. */
 size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
                                     int32_t P, int32_t max_pages_per_seq, int32_t dtype,
                                     int32_t num_workgroups);

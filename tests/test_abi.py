@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_version_and_error_strings():
-    assert idlm.idlm_version() == 200
+    assert idlm.idlm_version() == 201
     seen = set()
     for code in range(0, -8, -1):
         msg = idlm.idlm_strerror(code)

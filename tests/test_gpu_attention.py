@@ -142,6 +142,20 @@ def test_row_paddings_and_group_sizes(S, Hq, Hkv):
         _check(inp, num_workgroups=nwg)
 
 
+@pytest.mark.parametrize("S,G,Hkv", [(13, 5, 2), (12, 8, 3), (16, 8, 2), (26, 5, 1), (25, 8, 2), (32, 8, 3), (32, 4, 8)])
+def test_more_than_64_rows_per_kv_head(S, G, Hkv):
+    """S*G = 65 .. 256 query rows per KV head with 128-wide heads run on the kernel whose wavefronts share the K/V
+    tiles of a workgroup through LDS: row counts that leave wavefronts partly or wholly without rows, one and two
+    row groups per KV head, contexts around tile and page edges, grids smaller than the number of (KV head, row
+    group) pairs (one workgroup walks several of them), grids of 16 and more (workgroup numbers are remapped in blocks
+    of 16) and the largest grid (about one tile per workgroup); both pool layouts, and K pages in operand order."""
+    ctx = [S, S + 1, 31 + S, 32 + S, 33 + S, 95 + S, 300, 1025, 64 + S]
+    for token_major in (False, True):
+        inp = _manual(len(ctx), S, Hkv * G, Hkv, ctx, seed=S * 10 + G, token_major=token_major)
+        for nwg in ((0, 1, 2, 5, 16, 64, 1024) if not token_major else (0, 3, 48)):
+            _check(inp, num_workgroups=nwg)
+
+
 @pytest.mark.parametrize("ctx", [[128], [129], [256], [257], [255], [383, 384, 385], [1024, 1, 513]])
 def test_tile_and_slice_boundaries(ctx):
     S = 1 if min(ctx) == 1 else 4
