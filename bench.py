@@ -272,6 +272,59 @@ def cpu_baseline(att, acc, cfg, n_seq, threads=0):
     }
 
 
+def wavefront_times(case, stream, launches=8):
+    """When the wavefronts of the attention main kernel start and finish (the library's debug trace on the device's
+    constant 100 MHz clock), summarised over `launches` launches: the launch lasts as long as its slowest wavefront."""
+    torch, idlm, cfg, att = case.torch, case.idlm, case.cfg, case.att
+    rec = torch.zeros(4096, 4, dtype=torch.int64, device=att.q.device)
+    idlm.idlm_isd_attention_wave_trace(rec)
+    runs = []
+    try:
+        for j in range(launches + 2):
+            q, k, v, _, out = case.sets[j % len(case.sets)]
+            rec.zero_()
+            idlm.idlm_isd_attention(q, k, v, att.block_table, att.ctx_lens, cfg.S, out, num_workgroups=case.workgroups,
+                                    workspace=case.ws_att, stream=stream, k_operand_order=case.kop)
+            torch.cuda.synchronize()
+            if j >= 2:
+                runs.append(rec.cpu().numpy().copy())
+    finally:
+        idlm.idlm_isd_attention_wave_trace(None)
+    keys = ("launch_us", "start_last_us", "finish_min_us", "finish_p10_us", "finish_median_us", "finish_p90_us",
+            "mean_idle_share", "finish_even_xcd_us", "finish_odd_xcd_us", "tiles_min", "tiles_mean", "tiles_max", "parts_mean",
+            "us_per_tile_median", "finish_by_parts")
+    acc = {k: [] for k in keys}
+    for r in runs:
+        act = r[:, 1] > 0
+        if not act.any():
+            continue
+        v = np.nonzero(act)[0]
+        t0 = r[act, 0].min()
+        start = (r[act, 0] - t0) / 100.0
+        end = (r[act, 1] - t0) / 100.0
+        tiles, parts = r[act, 2].astype(np.float64), r[act, 3]
+        xcd = (v // 4) % 8
+        acc["launch_us"].append(end.max()); acc["start_last_us"].append(start.max())
+        acc["finish_min_us"].append(end.min())
+        for name, q_ in (("finish_p10_us", 10), ("finish_median_us", 50), ("finish_p90_us", 90)):
+            acc[name].append(np.percentile(end, q_))
+        acc["mean_idle_share"].append(1.0 - end.mean() / end.max())
+        acc["finish_even_xcd_us"].append(end[xcd % 2 == 0].mean()); acc["finish_odd_xcd_us"].append(end[xcd % 2 == 1].mean())
+        acc["tiles_min"].append(tiles.min()); acc["tiles_mean"].append(tiles.mean()); acc["tiles_max"].append(tiles.max())
+        acc["parts_mean"].append(parts.mean())
+        acc["us_per_tile_median"].append(np.median((end - start) / np.maximum(tiles, 1)))
+        acc["finish_by_parts"].append({int(k_): float(end[parts == k_].mean()) for k_ in np.unique(parts)})
+    out = {k: float(np.mean(acc[k])) for k in keys if k != "finish_by_parts" and acc[k]}
+    by = {}
+    for d in acc["finish_by_parts"]:
+        for k_, x in d.items():
+            by.setdefault(k_, []).append(x)
+    out["mean_finish_us_by_sequence_parts"] = {str(k_): float(np.mean(x)) for k_, x in sorted(by.items())}
+    out["wavefronts"] = int((runs[-1][:, 1] > 0).sum()) if runs else 0
+    out["launches"] = len(runs)
+    return out
+
+
 def stream_probe(idlm, dev):
     """Plain streaming kernels of known size: practical bandwidth ceiling of this device, and the reference
     that hardware byte counters are scaled by in the committed profiles (4 GiB, so that the 256 MB memory-
@@ -489,14 +542,15 @@ def main():
     ap.add_argument("--k-operand-order", type=int, default=1,
                     help="1: the K pool's pages are kept in the attention kernel's operand order (IDLM_DTYPE_BF16_KOP)")
     ap.add_argument("--sections", default="all",
-                    help="comma list of step,probe,cpu,extras,configs (all = every one; configs only with the default workload)")
+                    help="comma list of step,probe,cpu,extras,configs,wavefronts (all = every one; configs only with the default workload)")
     ap.add_argument("--copies", type=int, default=0, help="input copies the launches rotate over (0 = as many as the "
                                                           "memory-side cache needs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); --gpus %d is not supported"
                  % args.gpus)
-    sections = {"step", "probe", "cpu", "extras", "configs"} if args.sections == "all" else set(args.sections.split(","))
+    sections = ({"step", "probe", "cpu", "extras", "configs", "wavefronts"} if args.sections == "all"
+                else set(args.sections.split(",")))
 
     import torch
     if not torch.cuda.is_available():
@@ -614,6 +668,8 @@ def main():
         line["stream_ceiling"] = stream_probe(idlm, dev)
         for name in (att_name, "isd_row_stats_kernel"):
             kernels[name]["frac_of_measured_stream_read"] = kernels[name]["GBps"] / line["stream_ceiling"]["read_GBps"]
+    if "wavefronts" in sections and cfg.dtype == "bf16":
+        line["attention_wavefront_times"] = wavefront_times(case, stream)
     if "extras" in sections:
         line.update(extras(case, args, hev, stream, dev, ms_per_step))
     if "cpu" in sections and args.cpu_sample > 0:

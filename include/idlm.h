@@ -36,7 +36,7 @@
 extern "C" {
 #endif
 
-#define IDLM_VERSION 201 /* major*10000 + minor*100 + patch */
+#define IDLM_VERSION 202 /* major*10000 + minor*100 + patch */
 
 enum {
     IDLM_OK = 0,

@@ -65,6 +65,17 @@ int idlm_isd_rng_dump(uint64_t rng_seed, uint32_t rng_offset, int32_t stream_tag
                       int32_t V, float* uniforms, float* gumbels, void* stream);
 
 /*
+ * idlm_isd_attention_wave_trace - measurement aid: from this call on every idlm_isd_attention of the process (bf16 path)
+ * whose grid has at most `records` wavefronts writes, per wavefront v of its main kernel, four 64-bit words to
+ * records_out[4 v ..]: the time the wavefront started and the time it finished (the device's constant 100 MHz clock,
+ * common to all compute units), the number of 32-token tiles it worked on and the number of sequence parts they
+ * belonged to.  Wavefronts without tiles write nothing: clear the array before the call.  Wavefront v belongs to
+ * workgroup v / 4.  records_out is device memory of 32 * records bytes that stays valid until tracing is switched
+ * off with (NULL, 0).  Not part of a step and not thread-safe: a process-wide setting, read when a call is launched.
+ */
+int idlm_isd_attention_wave_trace(uint64_t* records_out, size_t records);
+
+/*
  * Measurement aid: copies n_bytes from src to dst with 16-byte loads and stores (n_bytes a
  * multiple of 16, both 16-byte aligned).  Used to calibrate hardware byte counters and to
  * measure the streaming bandwidth actually reachable on the device.  Same stream / error

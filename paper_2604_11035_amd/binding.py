@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
         L.idlm_version.restype = C.c_int
         L.idlm_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.idlm_stream_copy.restype = C.c_int
+        L.idlm_isd_attention_wave_trace.argtypes = [vp, C.c_size_t]
+        L.idlm_isd_attention_wave_trace.restype = C.c_int
         L.idlm_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.idlm_stream_read.restype = C.c_int
         _lib = L
@@ -241,6 +243,18 @@ def idlm_stream_copy(src, dst, stream=None):
     rc = lib().idlm_stream_copy(_ptr(src), _ptr(dst), n, _stream(stream))
     if rc != 0:
         raise IdlmError(rc, "idlm_stream_copy")
+
+
+def idlm_isd_attention_wave_trace(records=None):
+    """Switches the per-wavefront trace of the attention main kernel on (records: int64 device tensor [n, 4], kept
+    alive by the caller while tracing is on) or off (None)."""
+    if records is None:
+        rc = lib().idlm_isd_attention_wave_trace(None, 0)
+    else:
+        assert records.dtype == torch.int64 and records.is_contiguous() and records.dim() == 2 and records.shape[1] == 4
+        rc = lib().idlm_isd_attention_wave_trace(_ptr(records), records.shape[0])
+    if rc != 0:
+        raise IdlmError(rc, "idlm_isd_attention_wave_trace")
 
 
 def idlm_stream_read(src, sink, stream=None):

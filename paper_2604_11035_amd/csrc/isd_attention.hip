@@ -60,6 +60,8 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     extern __shared__ u32x4 qlds_all[];   // [wavefront][(nb*KS + s)*64 + lane] Q operands of the current item
     __shared__ TilePlan plan;
 
+    const unsigned long long t_start = p.wave_trace ? __builtin_amdgcn_s_memrealtime() : 0ull;
+    int traced_tiles = 0, traced_parts = 0;
     const int total_weight = plan_scan(p, ctx_lens, plan);
     if (total_weight == kSeqCost * p.B) return;   // no tiles at all
     const int lane = threadIdx.x & 63;
@@ -72,12 +74,18 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     const int wv = blockIdx.x * 4 + w;
     const int slice = slice_of(wv);
     if (slice >= Wg) return;
-    int b0 = 0, pre0 = 0, b_end, pre_end;   // first sequence of the slice and the tiles before it
-    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, b0, pre0);
-    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, b_end, pre_end);
-    if (slice_begin >= slice_end) return;
-    const int vh0 = NW >= VH ? wv % VH : wv;
+    // Under saturation the wavefronts on odd XCDs (workgroup number odd) get about 6 % less of the memory system than those on
+    // even ones.  With a multiple of eight virtual heads the parity of a wavefront's XCD is bit 2 of its virtual head, the same
+    // for all slices of a head; so odd slices take the head whose number differs in bit 2 (the slices of every head then
+    // alternate between the two kinds of XCD) and the slices on even XCDs are made longer by the share p.xcd_bias / 1024.
+    const bool balanced = p.xcd_bias != 0;
+    const int vh0 = NW >= VH ? (wv % VH) ^ (balanced ? 4 * (slice & 1) : 0) : wv;
     const int vstep = NW >= VH ? VH : NW;
+    const int odd_shift = balanced ? ((vh0 & 4) ? -p.xcd_bias : p.xcd_bias) : 0;
+    int b0 = 0, pre0 = 0, b_end, pre_end;   // first sequence of the slice and the tiles before it
+    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, b0, pre0, odd_shift);
+    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, b_end, pre_end, odd_shift);
+    if (slice_begin >= slice_end) return;
 
     const int n = lane & 15, g = lane >> 4;
     const int S = p.S, G = p.G, M = p.M;
@@ -235,7 +243,9 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
                 store_rows(bb, nb, c);
             }
         };
+        traced_tiles += remaining;
         for (int i = 0; i < remaining;) {
+            ++traced_parts;
             // ---- a sequence starts (or continues from an earlier slice); its Q is in this wavefront's
             //      LDS already, the accumulators restart ----
             const int n_in = min(nt - kt, remaining - i);   // tiles of this sequence inside the slice
@@ -666,6 +676,7 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
         if (kParkSlots > 1 && nparked > 1) flush_parked(park1, park_b1);
         if (stash_slot >= 0) flush_stash(stash_slot);
     }
+    wave_trace_write(p, wv, t_start, traced_tiles, traced_parts);
 }
 
 // Joins the partials of sequences that span several wavefront slices.  Block (vh, j) looks at the
@@ -683,12 +694,15 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int VH = p.Hkv * p.RG;
     const int vh = blockIdx.x % VH;
     const int jcut = blockIdx.x / VH + 1;          // cut = start of slice jcut
+    // the main kernel's partition: shifted odd cuts and heads that alternate with the slice, if it balances the XCDs
+    const bool balanced = p.xcd_bias != 0;
+    const int odd_shift = balanced ? ((vh & 4) ? -p.xcd_bias : p.xcd_bias) : 0;
     auto slice_start = [&](int j) {
         int bb, pp;
-        return slice_first_tile(p, ctx_lens, plan, total_weight, Wg, j, bb, pp);
+        return slice_first_tile(p, ctx_lens, plan, total_weight, Wg, j, bb, pp, odd_shift);
     };
     int b = 0, pre = 0;
-    const int cut = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, jcut, b, pre);
+    const int cut = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, jcut, b, pre, odd_shift);
     if (cut <= 0 || cut >= total) return;
     const int ntiles = seq_tiles(p, ctx_lens, b);
     if (cut == pre) return;                        // the cut coincides with the start of a sequence
@@ -697,7 +711,9 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     if (first_begin > item_begin) return;          // an earlier cut is inside the same sequence
     // slices jcut-1 .. hold this sequence's partials, written by wavefront j*VH + vh into slot 2v if
     // the sequence is the first one of that slice (the slice starts inside it), 2v+1 if it is its last
-    auto slot_of = [&](int j, int jbeg) { return 2 * (j * VH + vh) + (jbeg >= item_begin ? 0 : 1); };
+    auto slot_of = [&](int j, int jbeg) {
+        return 2 * (j * VH + (vh ^ (balanced ? 4 * (j & 1) : 0))) + (jbeg >= item_begin ? 0 : 1);
+    };
     const int kvh = vh / p.RG;
     const int rowbase = (vh - kvh * p.RG) * rows_per_group;
     const int nrows = min(rows_per_group, p.M - rowbase);
@@ -877,6 +893,8 @@ static bool shapes_ok(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D, 
     return true;
 }
 
+constexpr int kXcdBias = 48;
+
 // More than 64 rows per KV head with 128-wide heads go to the kernel whose wavefronts share the K/V tiles through
 // LDS (its tile is built for D = 128): workgroups of four wavefronts with 32 rows each, two workgroups per compute unit
 static bool uses_shared_kernel(int M, int D) { return D == 128 && M > 64; }
@@ -928,6 +946,19 @@ static size_t partial_slots_bytes(int NB, int W, int waves_per_workgroup, int D)
 {
     const size_t slots = (size_t)2 * W * waves_per_workgroup;
     return slots * NB * (4 * 64 * (size_t)(D / 8) + 16 * sizeof(f32x4));
+}
+
+// per-wavefront trace records of the main kernel (idlm_isd_attention_wave_trace): a process-wide debug setting
+static unsigned long long* g_wave_trace = nullptr;
+static size_t g_wave_trace_records = 0;
+
+extern "C" int idlm_isd_attention_wave_trace(uint64_t* records_out, size_t records)
+{
+    if ((records_out == nullptr) != (records == 0)) return IDLM_ERR_NULL;
+    if (!aligned(records_out, 8)) return IDLM_ERR_ALIGN;
+    g_wave_trace = reinterpret_cast<unsigned long long*>(records_out);
+    g_wave_trace_records = records;
+    return IDLM_OK;
 }
 
 extern "C" size_t idlm_isd_attention_workspace(int32_t B, int32_t S, int32_t Hq, int32_t Hkv, int32_t D,
@@ -1027,6 +1058,14 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.RG = RG_;
     p.Mpad = 16 * NB;
     p.partial_layout = shared ? 1 : 0;
+    p.wave_trace = (size_t)W * wpw <= g_wave_trace_records ? g_wave_trace : nullptr;
+    {
+        // slices on even XCDs take over 48 / 1024 of a slice from those on odd ones where the mapping allows it (measured:
+        // the two kinds of wavefront then finish together; 40 .. 56 are equally good)
+        const int VHq = Hkv * p.RG, NWq = W * wpw;
+        const int Wgq = NWq >= VHq ? NWq / VHq : 1;
+        p.xcd_bias = (!shared && VHq % 8 == 0 && NWq >= VHq && Wgq % 2 == 0) ? kXcdBias : 0;
+    }
     const size_t slots = (size_t)2 * W * wpw;
     p.ws_o = workspace;
     p.ws_ml = reinterpret_cast<f32x4*>(static_cast<char*>(workspace) + slots * NB * 4 * 64 * (size_t)(D / 8));

@@ -27,6 +27,9 @@ struct AttnParams {
     int B, S, Hq, Hkv, G, M, RG, max_pages, Mpad;   // RG groups of Mpad = 16*NB rows share a KV head
     int num_pages;
     int partial_layout;   // which values an entry of a partial result holds: 0 = streaming kernel, 1 = shared-tile kernel
+    int xcd_bias;   // streaming kernel: 1024 x the share of a slice that wavefronts on even XCDs take over from those on odd
+                    // ones (0 = equal slices); only with a multiple of eight virtual heads and an even number of slices
+    unsigned long long* wave_trace;   // nullptr, or [wavefronts of the grid][4]: start, end (100 MHz clock), tiles, sequence parts
     int64_t page_stride, head_stride, token_stride;
     float scale_log2;
 };
@@ -164,14 +167,16 @@ __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* 
 
 // First tile (position in the head's tile list) of slice j of Wg, the sequence b that holds it
 // and the tiles before b.  j >= Wg gives the end of the list (b and pre are then not set).
-// Wavefront-level like plan_locate.
+// odd_shift moves the starts of the odd slices by odd_shift / 1024 of a slice (slices 2i grow and slices 2i + 1
+// shrink by that share, or the other way round for a negative value).  Wavefront-level like plan_locate.
 template <int NWAVES>
 __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32_t* __restrict__ ctx_lens,
-                                                const TilePlanT<NWAVES>& plan, int total_weight, int Wg, int j, int& b, int& pre)
+                                                const TilePlanT<NWAVES>& plan, int total_weight, int Wg, int j, int& b, int& pre,
+                                                int odd_shift = 0)
 {
     const int total_tiles = total_weight - kSeqCost * p.B;
     if (j >= Wg) return total_tiles;
-    const int y = (int)((int64_t)total_weight * j / Wg);
+    const int y = (int)((int64_t)total_weight * (1024 * (int64_t)j + ((j & 1) ? odd_shift : 0)) / (1024 * (int64_t)Wg));
     int before;
     plan_locate(p, ctx_lens, plan, y, b, before);
     pre = before - kSeqCost * b;
@@ -184,6 +189,19 @@ __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32
         nt = seq_tiles(p, ctx_lens, b);
     }
     return x;
+}
+
+// Debug aid (idlm_isd_attention_wave_trace): what a wavefront did and when, on the constant 100 MHz clock that all compute
+// units share.  A wavefront that has no tiles writes nothing (the host clears the array).
+__device__ __forceinline__ void wave_trace_write(const AttnParams& p, int wavefront, unsigned long long t_start, int tiles, int parts)
+{
+    if (p.wave_trace != nullptr && (threadIdx.x & 63) == 0) {
+        unsigned long long* r = p.wave_trace + 4 * (size_t)wavefront;
+        r[0] = t_start;
+        r[1] = __builtin_amdgcn_s_memrealtime();
+        r[2] = (unsigned long long)tiles;
+        r[3] = (unsigned long long)parts;
+    }
 }
 
 // A lane's share of a V row (and of an output row) is a chunk of D/16 consecutive values, 8 or 16 bytes.

@@ -71,6 +71,8 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
     extern __shared__ __attribute__((aligned(1024))) u32x4 smem[];   // [kRing] tiles of K (8 operand blocks of 1 KB) and V (32 rows of 256 bytes)
     __shared__ TilePlan plan;
 
+    const unsigned long long t_start = p.wave_trace ? __builtin_amdgcn_s_memrealtime() : 0ull;
+    int traced_tiles = 0, traced_parts = 0;
     const int total_weight = plan_scan(p, ctx_lens, plan);
     if (total_weight == kSeqCost * p.B) return;   // no tiles at all
     const int lane = threadIdx.x & 63;
@@ -223,7 +225,9 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
         ring_barrier();
         if (has_rows) read_k(0);
 
+        traced_tiles += remaining;
         for (int i = 0; i < remaining;) {
+            ++traced_parts;
             // ---- a sequence starts (or continues from an earlier slice) ----
             const int n_in = min(nt - kt, remaining - i);   // tiles of this sequence inside the slice
             const bool first_of_slice = i == 0;
@@ -436,6 +440,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
         dma_wait<0>();
         ring_barrier();
     }
+    wave_trace_write(p, (int)blockIdx.x * kSharedWaves + w, t_start, traced_tiles, traced_parts);
 }
 
 // ---- host side ----

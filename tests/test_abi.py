@@ -32,12 +32,12 @@ def test_every_declared_symbol_is_exported():
     main = set(declared_functions([os.path.join(INCLUDE, "idlm.h")]))
     aids = set(declared_functions([os.path.join(INCLUDE, "idlm_debug.h")])) - main
     assert aids == {"idlm_isd_attention_ev", "idlm_isd_accept_ev", "idlm_isd_accept_bf16_ev", "idlm_isd_rng_dump",
-                    "idlm_stream_copy", "idlm_stream_read"}
+                    "idlm_isd_attention_wave_trace", "idlm_stream_copy", "idlm_stream_read"}
     assert not any(n.endswith("_ev") or n.startswith("idlm_stream") for n in main)
 
 
 def test_version_and_error_strings():
-    assert idlm.idlm_version() == 201
+    assert idlm.idlm_version() == 202
     seen = set()
     for code in range(0, -8, -1):
         msg = idlm.idlm_strerror(code)

@@ -187,6 +187,39 @@ def test_bf16_head_dimension_64_at_the_8b_shape():
     _check(inp)
 
 
+@pytest.mark.parametrize("S,G,Hkv", [(8, 4, 8), (16, 8, 2)])
+def test_wavefront_trace_accounts_for_every_tile(S, G, Hkv):
+    """The debug trace of the main kernel (one record per wavefront: start, end, tiles, sequence parts): every 32-token tile
+    of every KV head's list is worked on exactly once per group of query rows, whatever the partition (the streaming
+    kernel with its slices of unequal length on even and odd XCDs, and the kernel whose four wavefronts share a tile), and
+    switching the trace off leaves the records alone."""
+    import paper_2604_11035_amd as idlm
+    h = _helpers()
+    ctx = [S + 5, 100, 333, 1025, 64 + S, 700, 31 + S, 2000]
+    inp = _manual(len(ctx), S, Hkv * G, Hkv, ctx, seed=3)
+    tiles_per_head = sum((c + 31) // 32 for c in ctx)
+    shared = S * G > 64
+    rec = torch.zeros(4096, 4, dtype=torch.int64, device=DEV)
+    for nwg in (0, 16, 64):
+        rec.zero_()
+        idlm.idlm_isd_attention_wave_trace(rec)
+        try:
+            got = h.gpu_attention(inp, num_workgroups=nwg)
+        finally:
+            idlm.idlm_isd_attention_wave_trace(None)
+        r = rec.cpu().numpy()
+        act = r[:, 1] > 0
+        assert act.any() and (r[act, 1] >= r[act, 0]).all()
+        # streaming kernel (up to 64 rows per KV head): one wavefront per slice; shared-tile kernel: the four wavefronts
+        # of a workgroup report the same tiles, one or two workgroup-level row groups per KV head
+        expect = tiles_per_head * Hkv * ((4 * (1 if S * G <= 128 else 2)) if shared else 1)
+        assert int(r[act, 2].sum()) == expect, (nwg, int(r[act, 2].sum()), expect)
+        assert (r[act, 3] >= 1).all()
+        before = r.copy()
+        again = h.gpu_attention(inp, num_workgroups=nwg)      # tracing is off: the records stay as they are
+        assert np.array_equal(rec.cpu().numpy(), before) and np.array_equal(again, got)
+
+
 def test_fp32_path_shapes():
     for D in (64, 128):
         inp = _manual(3, 4, 4, 2, [4, 37, 120], dtype=torch.float32, D=D, seed=D)
