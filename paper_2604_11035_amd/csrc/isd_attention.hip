@@ -81,10 +81,9 @@ __global__ __launch_bounds__(256) void isd_attention_bf16_kernel(const AttnParam
     const bool balanced = p.xcd_bias != 0;
     const int vh0 = NW >= VH ? (wv % VH) ^ (balanced ? 4 * (slice & 1) : 0) : wv;
     const int vstep = NW >= VH ? VH : NW;
-    const int odd_shift = balanced ? ((vh0 & 4) ? -p.xcd_bias : p.xcd_bias) : 0;
     int b0 = 0, pre0 = 0, b_end, pre_end;   // first sequence of the slice and the tiles before it
-    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, b0, pre0, odd_shift);
-    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, b_end, pre_end, odd_shift);
+    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, vh0, b0, pre0);
+    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, vh0, b_end, pre_end);
     if (slice_begin >= slice_end) return;
 
     const int n = lane & 15, g = lane >> 4;
@@ -694,15 +693,14 @@ __global__ __launch_bounds__(256) void isd_attention_merge_kernel(const AttnPara
     const int VH = p.Hkv * p.RG;
     const int vh = blockIdx.x % VH;
     const int jcut = blockIdx.x / VH + 1;          // cut = start of slice jcut
-    // the main kernel's partition: shifted odd cuts and heads that alternate with the slice, if it balances the XCDs
+    // the main kernel's partition: slices of unequal length, and (streaming kernel) heads that alternate with the slice
     const bool balanced = p.xcd_bias != 0;
-    const int odd_shift = balanced ? ((vh & 4) ? -p.xcd_bias : p.xcd_bias) : 0;
     auto slice_start = [&](int j) {
         int bb, pp;
-        return slice_first_tile(p, ctx_lens, plan, total_weight, Wg, j, bb, pp, odd_shift);
+        return slice_first_tile(p, ctx_lens, plan, total_weight, Wg, j, vh, bb, pp);
     };
     int b = 0, pre = 0;
-    const int cut = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, jcut, b, pre, odd_shift);
+    const int cut = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, jcut, vh, b, pre);
     if (cut <= 0 || cut >= total) return;
     const int ntiles = seq_tiles(p, ctx_lens, b);
     if (cut == pre) return;                        // the cut coincides with the start of a sequence

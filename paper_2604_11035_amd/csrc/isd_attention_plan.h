@@ -165,18 +165,25 @@ __device__ __forceinline__ void plan_locate(const AttnParams& p, const int32_t* 
     before = __builtin_amdgcn_readlane(fpre, src);
 }
 
-// First tile (position in the head's tile list) of slice j of Wg, the sequence b that holds it
-// and the tiles before b.  j >= Wg gives the end of the list (b and pre are then not set).
-// odd_shift moves the starts of the odd slices by odd_shift / 1024 of a slice (slices 2i grow and slices 2i + 1
-// shrink by that share, or the other way round for a negative value).  Wavefront-level like plan_locate.
+// Where slice j of virtual head vh starts, in 1/1024 of a mean slice: the odd cuts are shifted by p.xcd_bias, so that slices 2i
+// grow and slices 2i + 1 shrink, or the other way round for the heads whose bit 2 is set (they start on an odd XCD).
+__device__ __forceinline__ int64_t slice_cut_numerator(const AttnParams& p, int vh, int j)
+{
+    const int shift = (vh & 4) ? -p.xcd_bias : p.xcd_bias;
+    return 1024 * (int64_t)j + ((j & 1) ? shift : 0);
+}
+
+// First tile (position in the head's tile list) of slice j of the Wg slices of virtual head vh, the sequence b that
+// holds it and the tiles before b.  j >= Wg gives the end of the list (b and pre are then not set).
+// Wavefront-level like plan_locate.
 template <int NWAVES>
 __device__ __forceinline__ int slice_first_tile(const AttnParams& p, const int32_t* __restrict__ ctx_lens,
-                                                const TilePlanT<NWAVES>& plan, int total_weight, int Wg, int j, int& b, int& pre,
-                                                int odd_shift = 0)
+                                                const TilePlanT<NWAVES>& plan, int total_weight, int Wg, int j, int vh,
+                                                int& b, int& pre)
 {
     const int total_tiles = total_weight - kSeqCost * p.B;
     if (j >= Wg) return total_tiles;
-    const int y = (int)((int64_t)total_weight * (1024 * (int64_t)j + ((j & 1) ? odd_shift : 0)) / (1024 * (int64_t)Wg));
+    const int y = (int)((int64_t)total_weight * slice_cut_numerator(p, vh, j) / (1024 * (int64_t)Wg));
     int before;
     plan_locate(p, ctx_lens, plan, y, b, before);
     pre = before - kSeqCost * b;

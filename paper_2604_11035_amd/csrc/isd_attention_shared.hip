@@ -90,8 +90,8 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
     // every wavefront looks the slice up for itself: the same values in all eight, so that they take the same
     // number of barriers
     int b0 = 0, pre0 = 0, b_end, pre_end;
-    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, b0, pre0);
-    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, b_end, pre_end);
+    const int slice_begin = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice, 0, b0, pre0);
+    const int slice_end = slice_first_tile(p, ctx_lens, plan, total_weight, Wg, slice + 1, 0, b_end, pre_end);
     if (slice_begin >= slice_end) return;
     const int remaining = slice_end - slice_begin;
     const int vh0 = NG >= VHW ? wg % VHW : wg;
