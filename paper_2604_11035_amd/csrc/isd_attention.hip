@@ -1058,11 +1058,12 @@ extern "C" int idlm_isd_attention_ev(const void* q, const void* k_cache, const v
     p.partial_layout = shared ? 1 : 0;
     p.wave_trace = (size_t)W * wpw <= g_wave_trace_records ? g_wave_trace : nullptr;
     {
-        // slices on even XCDs take over 48 / 1024 of a slice from those on odd ones where the mapping allows it (measured:
-        // the two kinds of wavefront then finish together; 40 .. 56 are equally good)
+        // With the K pages in operand order, slices on even XCDs take over 48 / 1024 of a slice from those on odd ones where the
+        // mapping allows it (measured: the two kinds of wavefront then finish together; 40 .. 56 are equally good).  With
+        // slot-major K pages the two kinds finish together as they are (and the kernel is not bound by the memory system alone).
         const int VHq = Hkv * p.RG, NWq = W * wpw;
         const int Wgq = NWq >= VHq ? NWq / VHq : 1;
-        p.xcd_bias = (!shared && VHq % 8 == 0 && NWq >= VHq && Wgq % 2 == 0) ? kXcdBias : 0;
+        p.xcd_bias = (!shared && dtype == IDLM_DTYPE_BF16_KOP && VHq % 8 == 0 && NWq >= VHq && Wgq % 2 == 0) ? kXcdBias : 0;
     }
     const size_t slots = (size_t)2 * W * wpw;
     p.ws_o = workspace;

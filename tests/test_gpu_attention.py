@@ -29,9 +29,18 @@ def _check(inp, num_workgroups=0, sel=None, scale=0.0, tol=None):
     # operand type (2^-9 of a few dominant terms, relative to the vector's scale rather than the element's)
     assert excess <= (1.5e-2 if inp.q.dtype == torch.bfloat16 else 1e-4), excess
     if inp.q.dtype == torch.bfloat16 and inp.k_cache.is_contiguous() and inp.q.shape[-1] == 128:
-        # the same K pool with its pages in operand order: other addresses, the same arithmetic, the same bits
+        # The same K pool with its pages in operand order: other addresses, the same arithmetic.  Where the tile list is cut
+        # at the same places in both layouts the bits are the same; with eight (or a multiple of eight) KV heads and up to
+        # 64 rows per KV head the operand-order launch cuts its slices unequally (longer ones on even XCDs), sequences are
+        # then split elsewhere, and the result is held to the oracle's tolerance like the first one.
         alt = h.gpu_attention(inp, num_workgroups=num_workgroups, scale=scale, k_operand_order=True)
-        assert np.array_equal(alt, got), "the operand-order K layout changed the result"
+        S_, Hq_, Hkv_ = inp.q.shape[1], inp.q.shape[2], inp.k_cache.shape[1]
+        if Hkv_ % 8 != 0 or S_ * (Hq_ // Hkv_) > 64:
+            assert np.array_equal(alt, got), "the operand-order K layout changed the result"
+        else:
+            rel_alt, _ = h.attention_errors(alt, ref)
+            assert rel_alt <= tol, "operand-order K pages: max relative error %g" % rel_alt
+            assert h.attention_elementwise_excess(alt, ref) <= 1.5e-2
     return got, ref
 
 
