@@ -229,6 +229,40 @@ def test_wavefront_trace_accounts_for_every_tile(S, G, Hkv):
         assert np.array_equal(rec.cpu().numpy(), before) and np.array_equal(again, got)
 
 
+def test_shared_tile_kernel_replays_from_a_captured_graph():
+    """The kernel for more than 64 rows per KV head allocates nothing and never synchronises either: captured in a HIP
+    graph, every replay (with Q refreshed in place and eager work in between) gives the bits of the eager call."""
+    import paper_2604_11035_amd as idlm
+    h = _helpers()
+    S, G, Hkv = 16, 8, 2
+    ctx = [S + 3, 90, 400, 1025, 64 + S, 700]
+    inp = _manual(len(ctx), S, Hkv * G, Hkv, ctx, seed=21)
+    B, D, P = len(ctx), 128, 16
+    ws = torch.empty(max(256, idlm.idlm_isd_attention_workspace(B, S, Hkv * G, Hkv, D, P, inp.block_table.shape[1], 1)),
+                     dtype=torch.uint8, device=DEV)
+    out = torch.zeros_like(inp.q)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        idlm.idlm_isd_attention(inp.q, inp.k_cache, inp.v_cache, inp.block_table, inp.ctx_lens, S, out, workspace=ws, stream=side)
+    torch.cuda.synchronize()
+    g = torch.Generator(device="cpu").manual_seed(5)
+    for rep in range(3):
+        inp.q.copy_(torch.randn(inp.q.shape, generator=g).to(torch.bfloat16))
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = h.bf16_to_f64(out)
+        eager = h.gpu_attention(inp)
+        assert np.array_equal(replayed, eager), rep
+        if rep == 0:
+            rel, _ = h.attention_errors(eager, h.oracle_attention(inp))
+            assert rel <= h.ATTN_REL_TOL
+        _ = (torch.randn(1 << 16, device=DEV) * 2).sum().item()      # unrelated eager work between replays
+
+
 def test_fp32_path_shapes():
     for D in (64, 128):
         inp = _manual(3, 4, 4, 2, [4, 37, 120], dtype=torch.float32, D=D, seed=D)
