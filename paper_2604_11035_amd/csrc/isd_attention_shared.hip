@@ -137,6 +137,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
         int qpos[NB];   // stride position i of this lane's row in each 16-row block
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) qpos[nb] = (rowbase + 16 * nb + n) / G;
+        const uint64_t page_bytes = 2 * (uint64_t)p.page_stride;
         const uint64_t kh = reinterpret_cast<uint64_t>(p.k + kvh * p.head_stride);
         const uint64_t vhp = reinterpret_cast<uint64_t>(p.v + kvh * p.head_stride);
 
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
             // a page id outside the pool breaks the caller's side of the contract; the read stays inside the pool anyway
             const int pg = min(max(id, 0), p.num_pages - 1);
             const uint32_t dst = ring_addr + (uint32_t)((issued & (kRing - 1)) * kTileBytes);
-            const uint64_t pb = 2 * (uint64_t)pg * (uint64_t)p.page_stride;
+            const uint64_t pb = (uint64_t)(uint32_t)pg * page_bytes;
             dma16(kh + pb, koff_a, dst + kdst);
             dma16(kh + pb, koff_b, dst + kdst + 1024);
             dma16(vhp + pb, voff_a, dst + vdst);
@@ -291,6 +292,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
                 const bool masked = tb + 32 > ctx - S + 1;
                 if (masked) {
                     asm volatile("s_nop 0");
+                    const int t0 = tb + 4 * opaque(g);   // first of this lane's tokens; hidden, or it is computed on every tile
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         const int lim = ctx - S + qpos[nb];   // last key this row may see
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
                         for (int tblk = 0; tblk < 2; ++tblk)
 #pragma unroll
                             for (int j = 0; j < 4; ++j)
-                                if (tb + 16 * tblk + 4 * g + j > lim) sacc[nb][tblk][j] = -INFINITY;
+                                if (t0 + 16 * tblk + j > lim) sacc[nb][tblk][j] = -INFINITY;
                     }
                 }
                 // ---- reference exponents: raised (and the accumulators rescaled) only when a score overshoots the
@@ -347,9 +349,10 @@ __global__ __launch_bounds__(256, 2) void isd_attention_shared_kernel(const Attn
                 if (masked) {
                     asm volatile("s_nop 0");
                     u32x4 keep;
+                    const int t0 = tb + 4 * opaque(g);
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
-                        const int tok = tb + 16 * (d >> 1) + 4 * g + 2 * (d & 1);
+                        const int tok = t0 + 16 * (d >> 1) + 2 * (d & 1);
                         keep[d] = (tok < ctx ? 0xffffu : 0u) | (tok + 1 < ctx ? 0xffff0000u : 0u);
                     }
 #pragma unroll
