@@ -26,7 +26,9 @@
 // 16-bit values held by one lane).  Q operands of the wavefront's current sequence sit in LDS.
 //
 // HBM-bound for S*G below the machine's flop/byte ridge: algorithmic traffic is one read of
-// the sequence's K and V rows (2 * Hkv * D * 2 bytes per context token).
+// the sequence's K and V rows (2 * Hkv * D * 2 bytes per context token).  This file holds the kernel for up to
+// 64 query rows per KV head (any bf16 shape at D = 64), the kernel that joins partial results, the fp32 path and
+// the entry points; more than 64 rows per KV head at D = 128 run on the kernel of isd_attention_shared.hip.
 #include "isd_attention_plan.h"
 
 namespace idlm {
