@@ -57,7 +57,8 @@ def test_accept_entry_points(name):
            idlm.idlm_isd_accept_filtered_workspace(B, S, V), outs)
 
 
-@pytest.mark.parametrize("name,kw", [("small", {}), ("small", {"B": 3}), ("8b", {})])
+# the last shape has 128 query rows per KV head: the kernel that shares the K/V tiles of a workgroup, two workgroups per CU
+@pytest.mark.parametrize("name,kw", [("small", {}), ("small", {"B": 3}), ("8b", {}), ("small", {"S": 32, "B": 6})])
 def test_attention(name, kw):
     cfg = get_config(name, **kw)
     att = make_attention_inputs(cfg, device=DEV)
