@@ -15,11 +15,12 @@
 //     is cut into slices of equal cost exactly as in the streaming kernel, but at WORKGROUP level.
 //   * K/V tiles go from global memory straight into an LDS ring of kRing tiles (global_load_lds_dwordx4: each
 //     lane's 16 bytes land at LDS base + 16 * lane, no registers involved).  A tile is 16 blocks of 1 KB (K: 16-token
-//     page x contraction step, in MFMA A-operand order; V: four 256-byte token rows); each wavefront requests four
-//     of them, up to kRing - 1 tiles ahead.
-//   * Per tile one barrier: a wavefront waits until its own requests of the tile have landed (the vector-memory
-//     counter retires in order), the barrier then says that all sixteen blocks are there AND that everybody has
-//     finished the previous tile, whose ring slot is requested anew right behind the barrier.
+//     page x contraction step, in MFMA A-operand order; V: four 256-byte token rows); each wavefront requests the
+//     four blocks of one 16-token page.
+//   * Per tile one barrier, which runs one tile ahead: before tile i a wavefront waits until its own requests of tile
+//     i + 1 have landed (the vector-memory counter retires in order; the requests of tile i + 2 stay in flight), and the
+//     barrier then says that all sixteen blocks of tile i + 1 are there AND that everybody has finished tile i - 1,
+//     whose ring slot takes the request of tile i + 3.  The K operands of tile i + 1 can so be read at the end of tile i.
 //   * Every wavefront reads the whole tile from LDS: K operands with lane-contiguous 16-byte reads, V operands with
 //     the transposing 8-byte read (ds_read_b64_tr_b16), which delivers Vt in A-operand order straight from token rows.
 //     Its Q rows stay in registers for the whole sequence.
@@ -36,7 +37,6 @@ constexpr int kSharedWaves = 4;     // wavefronts per workgroup, one per SIMD; t
 
 typedef __attribute__((address_space(3))) char* lds_bytes;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 // 16 bytes per lane from global memory (64-bit base in scalar registers + 32-bit byte offset per lane) straight
 // into LDS at byte address lds_addr + 16 * lane.  The compiler does not know that this is a memory instruction: it
