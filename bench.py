@@ -382,7 +382,16 @@ def extras(case, args, hev, stream, dev, ms_per_step):
         case.step(0, side)
     torch.cuda.synchronize()
     t_graph = timed(lambda: [graph.replay() for _ in range(args.steps)], n=1) / args.steps
-    res["launch_modes"] = {"timed_region_ms": ms_per_step, "eager_ms": t_plain, "graph_replay_ms": t_graph}
+    # four steps per graph: what a replay costs per launch of a graph, as against per kernel node
+    graph4 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph4, stream=side):
+        for j in range(4):
+            case.step(j, side)
+    torch.cuda.synchronize()
+    n4 = max(1, args.steps // 4)
+    t_graph4 = timed(lambda: [graph4.replay() for _ in range(n4)], n=1) / (4 * n4)
+    res["launch_modes"] = {"timed_region_ms": ms_per_step, "eager_ms": t_plain, "graph_replay_ms": t_graph,
+                           "graph_of_four_steps_replay_ms_per_step": t_graph4}
 
     # the attention call alone with the K pool in the other page layout (slot-major rows / operand order)
     if cfg.dtype == "bf16" and cfg.D == 128:
